@@ -1,0 +1,108 @@
+/*
+ * pcmm.h - C ABI of the MI355X (gfx950) plaintext-ciphertext matrix multiplication library.
+ *
+ * The operation.  The paper's linear layers (QKV, O, gate/up, down projections) are evaluated as
+ * PCMM, B = W.A with W a plaintext weight matrix and A encrypted activations (Section 5.1), through
+ * the reduction of PCMM to clear matrix products on ciphertext data (Section 2.2, "PCMM from BLAS";
+ * Section 3.2).  A ciphertext is a pair (a, b) in R_Q^2 and addition is component-wise (Appendix A),
+ * so the clear product acts on the coefficients of both components alike.  With Q in RNS form, for
+ * every limb j < L, row m < M and column n < Ncols this library computes
+ *
+ *     C_j[m][n] = ( sum_{k<K} W[m][k] * A_j[k][n] )  mod q_j ,   the representative in [0, q_j),
+ *
+ * exactly (bit-exact, deterministic).  Columns [0, Ncols/2) conventionally hold the coefficients of
+ * the a-components and [Ncols/2, Ncols) those of the b-components; the library does not care.
+ *
+ * Method (the part the paper leaves to a GPU BLAS): every residue is split into D signed base-256
+ * digits, W (int8, or int16 as two signed int8 slices) is multiplied with every digit plane by int8
+ * MFMA with int32 accumulation, and the epilogue recombines the digit products and Barrett-reduces
+ * modulo q_j.
+ *
+ * Conventions.  All matrices are dense row-major.  "device" pointers are HIP device memory on the
+ * plan's device; "host" pointers are ordinary host memory.  The library never frees, reallocates or
+ * keeps a caller's buffer.  No function throws or aborts; every failure is a status code.
+ */
+#ifndef PCMM_H
+#define PCMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pcmm_plan pcmm_plan; /* opaque; owns packed W, per-limb constants and digit scratch */
+
+typedef enum {
+    PCMM_OK = 0,
+    PCMM_EINVAL = 1,       /* null pointer, non-positive size, even or out-of-size prime, bad w_bits ... */
+    PCMM_EUNSUPPORTED = 2, /* valid request outside what the kernels cover (see pcmm_plan_create) */
+    PCMM_ENOMEM = 3,       /* host or device allocation failed */
+    PCMM_EDEVICE = 4       /* a HIP call or kernel launch failed */
+} pcmm_status;
+
+/*
+ * Build a plan for one weight matrix W and one list of primes (the paper's "model conversion"
+ * step, Section 5.3: a layout-only transformation of the weights, done once).
+ *
+ *   out          receives the plan (set to NULL on failure)
+ *   M, K         W is M x K:  M output channels, K input channels (contraction length)
+ *   Ncols        columns of every A_j and C_j (2N for ring degree N: both ciphertext components)
+ *   L            number of RNS limbs, 1 <= L <= 64
+ *   primes_host  [L] host array; each q_j odd with 2^(prime_bits-1) < q_j < 2^prime_bits
+ *   prime_bits   size of the primes, 10 <= prime_bits <= 62
+ *   w_bits       8: W is int8_t [M][K];  16: W is int16_t [M][K] with every entry in [-32768, 32639]
+ *                (so that its balanced high byte fits int8)
+ *   W_dev        device pointer to W, row-major; read during this call only, not kept
+ *   device       HIP device ordinal the plan lives on
+ *   stream       hipStream_t (NULL = default stream) used for the packing kernels; this call
+ *                synchronises that stream before returning
+ *
+ * PCMM_EUNSUPPORTED when: the int32 accumulators could overflow (needs (w_bits/8)*K <= 131071);
+ * or digits + slices - 1 > 8 (e.g. int16 W with primes above 54 bits).
+ * PCMM_EINVAL for an int16 W entry above 32639, and for everything listed under PCMM_EINVAL above.
+ */
+pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncols, int32_t L,
+                             const uint64_t *primes_host, int32_t prime_bits, int32_t w_bits,
+                             const void *W_dev, int32_t device, void *stream);
+
+/* Device bytes the plan owns (packed W + digit scratch + constants). 0 for NULL. */
+size_t pcmm_plan_workspace_bytes(const pcmm_plan *plan);
+
+/* Number of signed 8-bit digits each residue is split into (D), 0 for NULL. */
+int32_t pcmm_plan_digits(const pcmm_plan *plan);
+
+/*
+ * One PCMM: all L limbs, all Ncols columns (both ciphertext components).
+ *
+ *   A_dev   device, [L][K][Ncols] uint64; A_dev[j] holds residues in [0, q_j) - a caller
+ *           precondition, not checked; read only
+ *   C_dev   device, [L][M][Ncols] uint64; every entry is written; must not overlap A_dev
+ *   stream  hipStream_t the kernels are enqueued on (NULL = default stream)
+ *
+ * Asynchronous: returns after enqueueing; the caller synchronises the stream.  Two runs of the
+ * SAME plan must not overlap in time (they share the plan's digit scratch); runs of different
+ * plans may.  Launch failures are reported as PCMM_EDEVICE; faults inside a kernel surface at the
+ * caller's next synchronisation.
+ */
+pcmm_status pcmm_run(const pcmm_plan *plan, const uint64_t *A_dev, uint64_t *C_dev, void *stream);
+
+/*
+ * Same as pcmm_run, but brackets each kernel with HIP events on `stream`, synchronises, and
+ * reports the kernel durations in milliseconds: ms_out[0] = digit-split kernel, ms_out[1] =
+ * MFMA + epilogue kernel.  ms_out is a host array of 2 floats.  For measurement harnesses.
+ */
+pcmm_status pcmm_run_profiled(const pcmm_plan *plan, const uint64_t *A_dev, uint64_t *C_dev,
+                              void *stream, float *ms_out);
+
+/* Frees everything the plan owns.  The caller makes sure no run of the plan is still in flight. */
+void pcmm_plan_destroy(pcmm_plan *plan);
+
+/* Static, human-readable name of a status code. */
+const char *pcmm_status_str(pcmm_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PCMM_H */

@@ -1,0 +1,17 @@
+"""MI355X-native PCMM (plaintext-ciphertext matrix multiplication) for CKKS linear layers.
+
+Thin Python binding over the C-ABI library libpcmm.so (see include/pcmm.h); every step of the
+computation runs in the library's HIP kernels.  PyTorch is used for device memory and streams only.
+"""
+from .pcmm import (  # noqa: F401
+    PcmmError,
+    PcmmPlan,
+    load_library,
+    pcmm_plan_create,
+    pcmm_plan_destroy,
+    pcmm_plan_digits,
+    pcmm_plan_workspace_bytes,
+    pcmm_run,
+    pcmm_run_profiled,
+    pcmm_status_str,
+)

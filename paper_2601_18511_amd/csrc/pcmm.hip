@@ -1,0 +1,653 @@
+// PCMM for MI355X (gfx950): C_j = W . A_j mod q_j, batched over RNS limbs and both ciphertext
+// components (the clear matrix product that the paper's linear-layer PCMM reduces to, Sections 2.2,
+// 3.2 and 5.1; ciphertexts as pairs in R_Q^2 with component-wise addition, Appendix A).
+//
+// Three kernels:
+//   pack_w_kernel   (plan time)  W -> int8 slices in MFMA A-operand fragment order
+//   split_kernel    (every run)  uint64 residues -> D signed base-256 digit planes in MFMA
+//                                B-operand fragment order
+//   gemm_kernel     (every run)  v_mfma_i32_16x16x64_i8 main loop, then recombination of the digit
+//                                accumulators and Barrett reduction modulo q_j
+//
+// Fragment order.  One v_mfma_i32_16x16x64_i8 operand is 16 (rows or columns) x 64 (k) int8: lane l
+// of the wave holds the 16 bytes with index (l % 16) and k = 16*(l/16) .. 16*(l/16)+15.  Both
+// operands use the same k mapping, so an integer dot product does not depend on the order of k
+// inside a lane.  A "fragment" is the 1 KiB such an operand takes, stored [lane][16 bytes], so that
+// a wave fetches it with one 16-byte load per lane from contiguous memory.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <new>
+#include "../../include/pcmm.h"
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+constexpr int kFrag = 1024;   // bytes of one 16 x 64 int8 MFMA operand fragment
+constexpr int kXcd = 8;       // accelerator complex dies, each with its own L2
+
+// Per-limb constants of the epilogue.
+struct LimbConst {
+    uint64_t q;      // the prime
+    uint64_t mu;     // floor(2^64 / q)
+    uint64_t off;    // q * floor(2^62 / q): added to a signed value of magnitude < 2^62 to make it positive
+    uint64_t c32;    // 2^32 mod q
+    uint64_t c32s;   // floor(c32 * 2^64 / q)  (Shoup companion of c32)
+};
+
+// ------------------------------------------------------------------------------------------------
+// modular helpers (device)
+// ------------------------------------------------------------------------------------------------
+// u < 2^64, mu = floor(2^64/q).  qhat = floor(u*mu / 2^64) satisfies u/q - 2 < qhat <= u/q, hence
+// u - qhat*q is in [0, 2q) and one conditional subtraction gives the canonical residue.
+__device__ __forceinline__ uint64_t barrett_u64(uint64_t u, uint64_t q, uint64_t mu)
+{
+    uint64_t qhat = __umul64hi(u, mu);
+    uint64_t r = u - qhat * q;
+    return r >= q ? r - q : r;
+}
+
+// x < q < 2^63, c < q, cs = floor(c * 2^64 / q): returns x*c mod q (Shoup's constant multiplication).
+__device__ __forceinline__ uint64_t mulmod_shoup(uint64_t x, uint64_t c, uint64_t cs, uint64_t q)
+{
+    uint64_t qhat = __umul64hi(x, cs);
+    uint64_t r = x * c - qhat * q;
+    return r >= q ? r - q : r;
+}
+
+// ------------------------------------------------------------------------------------------------
+// plan-time kernel: pack W
+// ------------------------------------------------------------------------------------------------
+// Output Wp[s][mb][kb][lane][16]: slice s of W[mb*16 + lane%16][kb*64 + (lane/16)*16 + 0..15],
+// zero outside M x K.  int16 entries are split as w = lo + 256*hi with lo = sign-extended low byte;
+// err is set to 1 if some hi does not fit int8.
+template <typename WT, int S>
+__global__ __launch_bounds__(256) void pack_w_kernel(const WT *__restrict__ W, int8_t *__restrict__ Wp,
+                                                     int64_t M, int64_t K, int64_t MB, int64_t nkb,
+                                                     int *__restrict__ err)
+{
+    int64_t unit = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // one 16-byte lane slot
+    int64_t total = MB * nkb * 64;
+    if (unit >= total) return;
+    int lane = (int)(unit % 64);
+    int64_t kb = (unit / 64) % nkb;
+    int64_t mb = unit / (64 * nkb);
+    int64_t m = mb * 16 + (lane % 16);
+    int64_t k0 = kb * 64 + (lane / 16) * 16;
+    int8_t lo[16], hi[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        int64_t k = k0 + j;
+        int w = (m < M && k < K) ? (int)W[m * K + k] : 0;
+        int l = (int)(int8_t)(w & 0xFF);
+        int h = (w - l) >> 8;
+        lo[j] = (int8_t)l;
+        hi[j] = (int8_t)h;
+        if (S == 2 && (h < -128 || h > 127)) atomicExch(err, 1);
+    }
+    int8_t *dst = Wp + ((mb * nkb + kb) * 64 + lane) * 16;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) dst[j] = lo[j];
+    if (S == 2) {
+        int8_t *dst2 = dst + MB * nkb * kFrag;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) dst2[j] = hi[j];
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// run-time kernel 1: digit split
+// ------------------------------------------------------------------------------------------------
+// Balanced base-256 digits: with Bias = sum_{i<D} 128 * 256^i, the bytes of x + Bias, each xor 0x80,
+// read as int8, are digits s_i in [-128,127] with x = sum_i s_i 256^i (valid while x + Bias < 256^D).
+//
+// Output layout Ad[limb][ntile][kb][nt][d][lane][16]; fragment (nt, d) of chunk (limb, ntile, kb)
+// holds digit d of A[limb][kb*64 + (lane/16)*16 + 0..15][(ntile*NT + nt)*16 + lane%16], zero outside
+// K x Ncols.  One block = 4 waves = 64 columns x 64 k; wave g takes k-group g, lane = column.
+template <int D>
+__global__ __launch_bounds__(256) void split_kernel(const uint64_t *__restrict__ A, int8_t *__restrict__ Ad,
+                                                    int64_t K, int64_t Ncols, int64_t nkb, int64_t ntiles,
+                                                    int NT)
+{
+    const int lane = threadIdx.x & 63;
+    const int g = threadIdx.x >> 6;
+    const int64_t kb = blockIdx.y;
+    const int64_t limb = blockIdx.z;
+    const int64_t n = (int64_t)blockIdx.x * 64 + lane;
+    const int64_t nb = n >> 4;
+    if (nb >= ntiles * NT) return;
+
+    uint64_t bias = 0;
+#pragma unroll
+    for (int i = 0; i < D; ++i) bias |= (uint64_t)0x80 << (8 * i);
+
+    const int64_t k0 = kb * 64 + g * 16;
+    const uint64_t *src = A + (limb * K + k0) * Ncols + n;
+    uint32_t out[D][4];
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) out[d][i] = 0;
+
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        uint64_t x = (k0 + j < K && n < Ncols) ? src[(int64_t)j * Ncols] : 0;
+        uint64_t y = x + bias;
+#pragma unroll
+        for (int d = 0; d < D; ++d) out[d][j >> 2] |= (uint32_t)((y >> (8 * d)) & 0xFF) << (8 * (j & 3));
+    }
+
+    const int64_t ntile = nb / NT;
+    const int nt = (int)(nb % NT);
+    int8_t *chunk = Ad + ((limb * ntiles + ntile) * nkb + kb) * ((int64_t)NT * D * kFrag);
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        v4i v;
+        v.x = (int)(out[d][0] ^ 0x80808080u);
+        v.y = (int)(out[d][1] ^ 0x80808080u);
+        v.z = (int)(out[d][2] ^ 0x80808080u);
+        v.w = (int)(out[d][3] ^ 0x80808080u);
+        *reinterpret_cast<v4i *>(chunk + (nt * D + d) * kFrag + (g * 16 + (int)(n & 15)) * 16) = v;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// run-time kernel 2: int8 MFMA main loop + recombination + Barrett
+// ------------------------------------------------------------------------------------------------
+struct GemmArgs {
+    const int8_t *Wp;       // [S][MB][nkb][64][16]
+    const int8_t *Ad;       // [L][ntiles][nkb][NT][D][64][16]
+    uint64_t *C;            // [L][M][Ncols]
+    const LimbConst *lc;    // [L]
+    int64_t M, Ncols;
+    int64_t MB;             // padded M / 16
+    int nkb;                // padded K / 64
+    int mtiles, ntiles, L;
+    int gn;                 // n-tiles per raster group
+    int64_t per_xcd;        // work items per XCD
+    int64_t total;          // L * mtiles * ntiles
+};
+
+// Work-group tile: (WM waves x MT fragments x 16) rows by (NT x 16) columns, all D digit planes.
+// Each wave owns MT*16 rows and keeps E = D+S-1 int32 accumulators per output: accumulator e sums
+// the products W_slice_s x digit_d with s + d = e, which all carry the weight 256^e.
+// W fragments go global -> registers (each wave reads only its own rows); digit fragments are shared
+// by all waves and staged through LDS, double-buffered, one barrier per k-step of 64.
+template <int WM, int MT, int NT, int D, int S, bool SINGLE>
+__global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
+{
+    constexpr int E = D + S - 1;
+    constexpr int T = WM * 64;
+    constexpr int CH = NT * D * kFrag;            // bytes of one digit chunk (one k-step)
+    constexpr int UNITS = CH / 16;                // 16-byte units per chunk
+    constexpr int NLD = (UNITS + T - 1) / T;      // units per thread
+
+    __shared__ __attribute__((aligned(16))) int8_t lds[2][CH];
+
+    // ---- which tile: XCD-aware raster.  Work-groups are dealt round-robin to the 8 XCDs, so
+    // bid % 8 names the XCD; each XCD walks its own contiguous range of tiles, m fastest inside
+    // groups of gn n-tiles, so that the tiles resident on one XCD share W rows and digit columns
+    // in that XCD's L2.
+    const int64_t bid = blockIdx.x;
+    const int64_t t = (bid % kXcd) * a.per_xcd + bid / kXcd;
+    if (bid / kXcd >= a.per_xcd || t >= a.total) return;
+    const int64_t per_limb = (int64_t)a.mtiles * a.ntiles;
+    const int limb = (int)(t / per_limb);
+    const int64_t rem = t % per_limb;
+    const int64_t grp = rem / ((int64_t)a.gn * a.mtiles);
+    const int64_t within = rem % ((int64_t)a.gn * a.mtiles);
+    const int gcount = (int)min((int64_t)a.gn, a.ntiles - grp * a.gn);
+    const int tm = (int)(within / gcount);
+    const int tn = (int)(grp * a.gn + within % gcount);
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int nkb = a.nkb;
+
+    const int8_t *Adc = a.Ad + (((int64_t)limb * a.ntiles + tn) * nkb) * CH;
+    const int64_t mb0 = ((int64_t)tm * WM + wave) * MT;       // first 16-row block of this wave
+    const int8_t *Wpc = a.Wp + (mb0 * nkb) * kFrag + lane * 16;
+    const int64_t w_slice_stride = a.MB * nkb * kFrag;
+
+    v4i acc[MT][NT][E];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc[i][j][e] = (v4i){0, 0, 0, 0};
+
+    v4i wcur[S][MT], wnext[S][MT];
+    v4i stage[NLD];
+
+    // prologue: chunk 0 -> LDS buffer 0, W fragments of k-step 0 -> registers
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        int u = threadIdx.x + i * T;
+        if (u < UNITS) stage[i] = *reinterpret_cast<const v4i *>(Adc + (int64_t)u * 16);
+    }
+#pragma unroll
+    for (int s = 0; s < S; ++s)
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+            wcur[s][i] = *reinterpret_cast<const v4i *>(Wpc + s * w_slice_stride + ((int64_t)i * nkb) * kFrag);
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        int u = threadIdx.x + i * T;
+        if (u < UNITS) *reinterpret_cast<v4i *>(&lds[0][u * 16]) = stage[i];
+    }
+    __syncthreads();
+
+    for (int kb = 0; kb < nkb; ++kb) {
+        const int cur = kb & 1;
+        const bool more = kb + 1 < nkb;
+        if (more) {
+            const int8_t *src = Adc + (int64_t)(kb + 1) * CH;
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) {
+                int u = threadIdx.x + i * T;
+                if (u < UNITS) stage[i] = *reinterpret_cast<const v4i *>(src + (int64_t)u * 16);
+            }
+#pragma unroll
+            for (int s = 0; s < S; ++s)
+#pragma unroll
+                for (int i = 0; i < MT; ++i)
+                    wnext[s][i] = *reinterpret_cast<const v4i *>(Wpc + s * w_slice_stride +
+                                                                 ((int64_t)i * nkb + kb + 1) * kFrag);
+        }
+
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                v4i b = *reinterpret_cast<const v4i *>(&lds[cur][(j * D + d) * kFrag + lane * 16]);
+#pragma unroll
+                for (int s = 0; s < S; ++s)
+#pragma unroll
+                    for (int i = 0; i < MT; ++i)
+                        acc[i][j][d + s] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wcur[s][i], b, acc[i][j][d + s], 0, 0, 0);
+            }
+        }
+
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) {
+                int u = threadIdx.x + i * T;
+                if (u < UNITS) *reinterpret_cast<v4i *>(&lds[cur ^ 1][u * 16]) = stage[i];
+            }
+#pragma unroll
+            for (int s = 0; s < S; ++s)
+#pragma unroll
+                for (int i = 0; i < MT; ++i) wcur[s][i] = wnext[s][i];
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue.  Accumulator register r of lane l is output row 4*(l/16)+r, column l%16 of its
+    // 16 x 16 block.  value = sum_e acc_e 256^e = vlo + 2^32 vhi with vlo, vhi of magnitude < 2^56.
+    const LimbConst lc = a.lc[limb];
+    uint64_t *Cl = a.C + (int64_t)limb * a.M * a.Ncols;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            const int64_t n = ((int64_t)tn * NT + j) * 16 + (lane & 15);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int64_t m = (mb0 + i) * 16 + (lane >> 4) * 4 + r;
+                int64_t vlo = 0, vhi = 0;
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    int64_t v = (int64_t)acc[i][j][e][r];
+                    if (e < 4) vlo += v << (8 * e);
+                    else vhi += v << (8 * (e - 4));
+                }
+                uint64_t res;
+                if (SINGLE) {
+                    // plan guarantees |vlo + 2^32 vhi| < 2^62
+                    res = barrett_u64((uint64_t)(vlo + (vhi << 32)) + lc.off, lc.q, lc.mu);
+                } else {
+                    uint64_t rlo = barrett_u64((uint64_t)vlo + lc.off, lc.q, lc.mu);
+                    uint64_t rhi = barrett_u64((uint64_t)vhi + lc.off, lc.q, lc.mu);
+                    res = rlo + mulmod_shoup(rhi, lc.c32, lc.c32s, lc.q);
+                    if (res >= lc.q) res -= lc.q;
+                }
+                if (m < a.M && n < a.Ncols) Cl[m * a.Ncols + n] = res;
+            }
+        }
+    }
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------------
+struct pcmm_plan {
+    int64_t M, K, Ncols;
+    int L, prime_bits, w_bits, device;
+    int D, S;
+    int WM, MT, NT;          // tile configuration
+    bool single;             // one Barrett per output suffices
+    int64_t MB, nkb, mtiles, ntiles;
+    int8_t *Wp;              // device
+    int8_t *Ad;              // device digit scratch
+    LimbConst *lc;           // device
+    size_t bytes;
+    hipEvent_t ev[4];
+    bool have_ev;
+};
+
+namespace {
+
+typedef unsigned __int128 u128;
+
+struct DevGuard {
+    int prev;
+    bool ok;
+    explicit DevGuard(int dev) : prev(-1), ok(false)
+    {
+        if (hipGetDevice(&prev) != hipSuccess) return;
+        if (prev != dev && hipSetDevice(dev) != hipSuccess) return;
+        ok = true;
+    }
+    ~DevGuard()
+    {
+        int cur = -1;
+        if (prev >= 0 && hipGetDevice(&cur) == hipSuccess && cur != prev) (void)hipSetDevice(prev);
+    }
+};
+
+// Accumulator footprint limits the tile: MT*NT*E*4 accumulator registers per lane (NT = 2).
+constexpr int tile_mt(int E) { return E <= 5 ? 4 : 2; }
+
+template <int WM, int MT, int NT, int D, int S>
+hipError_t launch_gemm_ds(const pcmm_plan *p, const GemmArgs &ga, int64_t grid, hipStream_t st)
+{
+    if (p->single)
+        hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, true>), dim3((unsigned)grid), dim3(WM * 64), 0, st, ga);
+    else
+        hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, false>), dim3((unsigned)grid), dim3(WM * 64), 0, st, ga);
+    return hipGetLastError();
+}
+
+template <int D, int S>
+hipError_t launch_gemm_tile(const pcmm_plan *p, const GemmArgs &ga, int64_t grid, hipStream_t st)
+{
+    constexpr int MT = tile_mt(D + S - 1);
+    if (p->MT != MT || p->NT != 2) return hipErrorInvalidValue;
+    if (p->WM == 4) return launch_gemm_ds<4, MT, 2, D, S>(p, ga, grid, st);
+    if (p->WM == 2) return launch_gemm_ds<2, MT, 2, D, S>(p, ga, grid, st);
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_gemm(const pcmm_plan *p, const GemmArgs &ga, int64_t grid, hipStream_t st)
+{
+    if (p->S == 1) {
+        switch (p->D) {
+        case 4: return launch_gemm_tile<4, 1>(p, ga, grid, st);
+        case 5: return launch_gemm_tile<5, 1>(p, ga, grid, st);
+        case 6: return launch_gemm_tile<6, 1>(p, ga, grid, st);
+        case 7: return launch_gemm_tile<7, 1>(p, ga, grid, st);
+        case 8: return launch_gemm_tile<8, 1>(p, ga, grid, st);
+        }
+    } else {
+        switch (p->D) {
+        case 4: return launch_gemm_tile<4, 2>(p, ga, grid, st);
+        case 5: return launch_gemm_tile<5, 2>(p, ga, grid, st);
+        case 6: return launch_gemm_tile<6, 2>(p, ga, grid, st);
+        case 7: return launch_gemm_tile<7, 2>(p, ga, grid, st);
+        }
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_split(const pcmm_plan *p, const uint64_t *A, hipStream_t st)
+{
+    int64_t colblocks = (p->ntiles * p->NT * 16 + 63) / 64;
+    dim3 grid((unsigned)colblocks, (unsigned)p->nkb, (unsigned)p->L);
+    dim3 block(256);
+#define PCMM_SPLIT_CASE(DD)                                                                              \
+    case DD:                                                                                             \
+        hipLaunchKernelGGL((split_kernel<DD>), grid, block, 0, st, A, p->Ad, p->K, p->Ncols, p->nkb,     \
+                           p->ntiles, p->NT);                                                            \
+        break;
+    switch (p->D) {
+        PCMM_SPLIT_CASE(4)
+        PCMM_SPLIT_CASE(5)
+        PCMM_SPLIT_CASE(6)
+        PCMM_SPLIT_CASE(7)
+        PCMM_SPLIT_CASE(8)
+    default: return hipErrorInvalidValue;
+    }
+#undef PCMM_SPLIT_CASE
+    return hipGetLastError();
+}
+
+void choose_tiles(pcmm_plan *p)
+{
+    p->NT = 2;
+    p->MT = tile_mt(p->D + p->S - 1);
+    p->WM = (p->M > (int64_t)2 * p->MT * 16) ? 4 : 2;
+}
+
+pcmm_status run_impl(const pcmm_plan *p, const uint64_t *A, uint64_t *C, hipStream_t st, float *ms)
+{
+    DevGuard dg(p->device);
+    if (!dg.ok) return PCMM_EDEVICE;
+
+    GemmArgs ga;
+    ga.Wp = p->Wp;
+    ga.Ad = p->Ad;
+    ga.C = C;
+    ga.lc = p->lc;
+    ga.M = p->M;
+    ga.Ncols = p->Ncols;
+    ga.MB = p->MB;
+    ga.nkb = (int)p->nkb;
+    ga.mtiles = (int)p->mtiles;
+    ga.ntiles = (int)p->ntiles;
+    ga.L = p->L;
+    ga.total = (int64_t)p->L * p->mtiles * p->ntiles;
+    ga.per_xcd = (ga.total + kXcd - 1) / kXcd;
+    // concurrent tiles on one XCD (32 CUs) should form a block of about 4 m-tiles x 8 n-tiles
+    ga.gn = 8;
+    const int64_t grid = ga.per_xcd * kXcd;
+
+    if (ms && hipEventRecord(p->ev[0], st) != hipSuccess) return PCMM_EDEVICE;
+    if (launch_split(p, A, st) != hipSuccess) return PCMM_EDEVICE;
+    if (ms && (hipEventRecord(p->ev[1], st) != hipSuccess || hipEventRecord(p->ev[2], st) != hipSuccess))
+        return PCMM_EDEVICE;
+    if (launch_gemm(p, ga, grid, st) != hipSuccess) return PCMM_EDEVICE;
+    if (ms) {
+        if (hipEventRecord(p->ev[3], st) != hipSuccess) return PCMM_EDEVICE;
+        if (hipEventSynchronize(p->ev[3]) != hipSuccess) return PCMM_EDEVICE;
+        if (hipEventElapsedTime(&ms[0], p->ev[0], p->ev[1]) != hipSuccess) return PCMM_EDEVICE;
+        if (hipEventElapsedTime(&ms[1], p->ev[2], p->ev[3]) != hipSuccess) return PCMM_EDEVICE;
+    }
+    return PCMM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *pcmm_status_str(pcmm_status s)
+{
+    switch (s) {
+    case PCMM_OK: return "PCMM_OK";
+    case PCMM_EINVAL: return "PCMM_EINVAL: invalid argument";
+    case PCMM_EUNSUPPORTED: return "PCMM_EUNSUPPORTED: request outside the supported range";
+    case PCMM_ENOMEM: return "PCMM_ENOMEM: allocation failed";
+    case PCMM_EDEVICE: return "PCMM_EDEVICE: HIP call or kernel launch failed";
+    }
+    return "PCMM: unknown status";
+}
+
+pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncols, int32_t L,
+                             const uint64_t *primes_host, int32_t prime_bits, int32_t w_bits,
+                             const void *W_dev, int32_t device, void *stream)
+{
+    if (!out) return PCMM_EINVAL;
+    *out = nullptr;
+    if (!primes_host || !W_dev) return PCMM_EINVAL;
+    if (M <= 0 || K <= 0 || Ncols <= 0 || L <= 0 || L > 64) return PCMM_EINVAL;
+    if (M > (int64_t)1 << 24 || Ncols > (int64_t)1 << 30) return PCMM_EINVAL;
+    if (w_bits != 8 && w_bits != 16) return PCMM_EINVAL;
+    if (prime_bits < 10 || prime_bits > 62) return PCMM_EINVAL;
+    if (device < 0) return PCMM_EINVAL;
+    uint64_t qmax = 0;
+    for (int j = 0; j < L; ++j) {
+        uint64_t q = primes_host[j];
+        if ((q & 1) == 0) return PCMM_EINVAL;
+        if (q <= ((uint64_t)1 << (prime_bits - 1)) || q >= ((uint64_t)1 << prime_bits)) return PCMM_EINVAL;
+        if (q > qmax) qmax = q;
+    }
+    const int S = w_bits / 8;
+    if ((int64_t)S * K > 131071) return PCMM_EUNSUPPORTED;   // int32 headroom: S*K*2^14 < 2^31
+
+    // smallest D with (qmax - 1) + Bias_D < 256^D
+    int D = 0;
+    for (int d = 1; d <= 8; ++d) {
+        u128 bias = 0;
+        for (int i = 0; i < d; ++i) bias |= (u128)0x80 << (8 * i);
+        if ((u128)(qmax - 1) + bias < ((u128)1 << (8 * d))) { D = d; break; }
+    }
+    if (D == 0) return PCMM_EUNSUPPORTED;
+    if (D < 4) D = 4;   // kernels are built for 4..8 digits; spare top digits are zero
+    const int E = D + S - 1;
+    if (E > 8) return PCMM_EUNSUPPORTED;
+
+    pcmm_plan *p = new (std::nothrow) pcmm_plan();
+    if (!p) return PCMM_ENOMEM;
+    p->M = M; p->K = K; p->Ncols = Ncols; p->L = L;
+    p->prime_bits = prime_bits; p->w_bits = w_bits; p->device = device;
+    p->D = D; p->S = S;
+    p->Wp = nullptr; p->Ad = nullptr; p->lc = nullptr; p->bytes = 0; p->have_ev = false;
+    choose_tiles(p);
+    const int64_t BM = (int64_t)p->WM * p->MT * 16, BN = (int64_t)p->NT * 16;
+    p->mtiles = (M + BM - 1) / BM;
+    p->ntiles = (Ncols + BN - 1) / BN;
+    p->MB = p->mtiles * BM / 16;
+    p->nkb = (K + 63) / 64;
+
+    // can value = sum_e acc_e 256^e be reduced in one go?  |acc_e| <= K * sum_{s+d=e} 128 * dmax_d,
+    // dmax_d = 128 except for the top digit, which is at most top = ((qmax-1+Bias) >> 8(D-1)) - 128.
+    {
+        u128 bias = 0;
+        for (int i = 0; i < D; ++i) bias |= (u128)0x80 << (8 * i);
+        int64_t top = (int64_t)((((u128)(qmax - 1) + bias) >> (8 * (D - 1))) & 0xFF) - 128;
+        if (top < 1) top = 1;
+        u128 bound = 0;
+        for (int e = 0; e < E; ++e) {
+            u128 be = 0;
+            for (int s = 0; s < S; ++s) {
+                int d = e - s;
+                if (d < 0 || d >= D) continue;
+                be += (u128)K * 128 * (u128)(d == D - 1 ? top : 128);
+            }
+            bound += be << (8 * e);
+        }
+        p->single = bound < ((u128)1 << 62);
+    }
+
+    DevGuard dg(device);
+    if (!dg.ok) { delete p; return PCMM_EDEVICE; }
+    hipStream_t st = (hipStream_t)stream;
+
+    const size_t wp_bytes = (size_t)S * p->MB * p->nkb * kFrag;
+    const size_t ad_bytes = (size_t)L * p->ntiles * p->nkb * p->NT * D * kFrag;
+    const size_t lc_bytes = (size_t)L * sizeof(LimbConst);
+    int *err_dev = nullptr;
+    pcmm_status rc = PCMM_OK;
+    if (hipMalloc((void **)&p->Wp, wp_bytes) != hipSuccess || hipMalloc((void **)&p->Ad, ad_bytes) != hipSuccess ||
+        hipMalloc((void **)&p->lc, lc_bytes) != hipSuccess || hipMalloc((void **)&err_dev, sizeof(int)) != hipSuccess) {
+        (void)hipGetLastError();
+        rc = PCMM_ENOMEM;
+    }
+    p->bytes = wp_bytes + ad_bytes + lc_bytes;
+
+    if (rc == PCMM_OK) {
+        LimbConst h[64];
+        for (int j = 0; j < L; ++j) {
+            uint64_t q = primes_host[j];
+            h[j].q = q;
+            h[j].mu = (uint64_t)((((u128)1) << 64) / q);
+            h[j].off = q * (uint64_t)((((u128)1) << 62) / q);
+            h[j].c32 = (uint64_t)((((u128)1) << 32) % q);
+            h[j].c32s = (uint64_t)(((u128)h[j].c32 << 64) / q);
+        }
+        if (hipMemcpyAsync(p->lc, h, lc_bytes, hipMemcpyHostToDevice, st) != hipSuccess ||
+            hipMemsetAsync(err_dev, 0, sizeof(int), st) != hipSuccess ||
+            hipStreamSynchronize(st) != hipSuccess)   // h lives on this stack frame
+            rc = PCMM_EDEVICE;
+    }
+    if (rc == PCMM_OK) {
+        int64_t units = p->MB * p->nkb * 64;
+        dim3 grid((unsigned)((units + 255) / 256)), block(256);
+        if (w_bits == 8)
+            hipLaunchKernelGGL((pack_w_kernel<int8_t, 1>), grid, block, 0, st, (const int8_t *)W_dev, p->Wp, M, K,
+                               p->MB, p->nkb, err_dev);
+        else
+            hipLaunchKernelGGL((pack_w_kernel<int16_t, 2>), grid, block, 0, st, (const int16_t *)W_dev, p->Wp, M, K,
+                               p->MB, p->nkb, err_dev);
+        int err_host = 0;
+        if (hipGetLastError() != hipSuccess ||
+            hipMemcpyAsync(&err_host, err_dev, sizeof(int), hipMemcpyDeviceToHost, st) != hipSuccess ||
+            hipStreamSynchronize(st) != hipSuccess)
+            rc = PCMM_EDEVICE;
+        else if (err_host)
+            rc = PCMM_EINVAL;   // an int16 entry above 32639
+    }
+    if (rc == PCMM_OK) {
+        p->have_ev = true;
+        for (int i = 0; i < 4; ++i)
+            if (hipEventCreate(&p->ev[i]) != hipSuccess) {
+                for (int k = 0; k < i; ++k) (void)hipEventDestroy(p->ev[k]);
+                p->have_ev = false;
+                rc = PCMM_EDEVICE;
+                break;
+            }
+    }
+    if (err_dev) (void)hipFree(err_dev);
+    if (rc != PCMM_OK) {
+        if (p->Wp) (void)hipFree(p->Wp);
+        if (p->Ad) (void)hipFree(p->Ad);
+        if (p->lc) (void)hipFree(p->lc);
+        delete p;
+        return rc;
+    }
+    *out = p;
+    return PCMM_OK;
+}
+
+size_t pcmm_plan_workspace_bytes(const pcmm_plan *plan) { return plan ? plan->bytes : 0; }
+
+int32_t pcmm_plan_digits(const pcmm_plan *plan) { return plan ? plan->D : 0; }
+
+pcmm_status pcmm_run(const pcmm_plan *plan, const uint64_t *A_dev, uint64_t *C_dev, void *stream)
+{
+    if (!plan || !A_dev || !C_dev) return PCMM_EINVAL;
+    return run_impl(plan, A_dev, C_dev, (hipStream_t)stream, nullptr);
+}
+
+pcmm_status pcmm_run_profiled(const pcmm_plan *plan, const uint64_t *A_dev, uint64_t *C_dev, void *stream,
+                              float *ms_out)
+{
+    if (!plan || !A_dev || !C_dev || !ms_out) return PCMM_EINVAL;
+    return run_impl(plan, A_dev, C_dev, (hipStream_t)stream, ms_out);
+}
+
+void pcmm_plan_destroy(pcmm_plan *plan)
+{
+    if (!plan) return;
+    DevGuard dg(plan->device);
+    if (plan->have_ev)
+        for (int i = 0; i < 4; ++i) (void)hipEventDestroy(plan->ev[i]);
+    if (plan->Wp) (void)hipFree(plan->Wp);
+    if (plan->Ad) (void)hipFree(plan->Ad);
+    if (plan->lc) (void)hipFree(plan->lc);
+    delete plan;
+}
+
+}  // extern "C"

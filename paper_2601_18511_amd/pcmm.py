@@ -1,0 +1,150 @@
+"""ctypes binding of libpcmm.so: same names as the C ABI, argument marshalling only.
+
+There is no CPU fallback: if the HIP library cannot be loaded the import of a function fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch  # imported before the library so that both share one HIP runtime
+
+from . import build as _build
+
+PCMM_OK, PCMM_EINVAL, PCMM_EUNSUPPORTED, PCMM_ENOMEM, PCMM_EDEVICE = range(5)
+
+EXPORTED = (
+    "pcmm_plan_create",
+    "pcmm_plan_workspace_bytes",
+    "pcmm_plan_digits",
+    "pcmm_run",
+    "pcmm_run_profiled",
+    "pcmm_plan_destroy",
+    "pcmm_status_str",
+)
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+class PcmmError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        super().__init__("%s: %s" % (where, pcmm_status_str(status)))
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libpcmm.so (building it first only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build_library(force=True)
+    lib = ctypes.CDLL(_build.LIB)
+    vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+    lib.pcmm_plan_create.argtypes = [ctypes.POINTER(vp), i64, i64, i64, i32, vp, i32, i32, vp, i32, vp]
+    lib.pcmm_plan_create.restype = ctypes.c_int
+    lib.pcmm_plan_workspace_bytes.argtypes = [vp]
+    lib.pcmm_plan_workspace_bytes.restype = ctypes.c_size_t
+    lib.pcmm_plan_digits.argtypes = [vp]
+    lib.pcmm_plan_digits.restype = i32
+    lib.pcmm_run.argtypes = [vp, vp, vp, vp]
+    lib.pcmm_run.restype = ctypes.c_int
+    lib.pcmm_run_profiled.argtypes = [vp, vp, vp, vp, ctypes.POINTER(ctypes.c_float)]
+    lib.pcmm_run_profiled.restype = ctypes.c_int
+    lib.pcmm_plan_destroy.argtypes = [vp]
+    lib.pcmm_plan_destroy.restype = None
+    lib.pcmm_status_str.argtypes = [ctypes.c_int]
+    lib.pcmm_status_str.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def pcmm_status_str(status: int) -> str:
+    return load_library().pcmm_status_str(int(status)).decode()
+
+
+class PcmmPlan:
+    """Owner of one pcmm_plan handle."""
+
+    def __init__(self, handle: int, M: int, K: int, Ncols: int, L: int, device: int):
+        self.handle = handle
+        self.M, self.K, self.Ncols, self.L, self.device = M, K, Ncols, L, device
+
+    def destroy(self) -> None:
+        if self.handle:
+            load_library().pcmm_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def _stream_handle(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def pcmm_plan_create(W: torch.Tensor, primes: Sequence[int], prime_bits: int, Ncols: int, stream=None) -> PcmmPlan:
+    """Plan for the device tensor W ([M][K], int8 or int16) and the host list of primes."""
+    if not W.is_cuda or W.dim() != 2 or W.dtype not in (torch.int8, torch.int16) or not W.is_contiguous():
+        raise ValueError("W must be a contiguous 2-D int8 or int16 tensor on the GPU")
+    M, K = W.shape
+    L = len(primes)
+    arr = (ctypes.c_uint64 * max(L, 1))(*[int(q) for q in primes])
+    out = ctypes.c_void_p()
+    w_bits = 8 if W.dtype == torch.int8 else 16
+    with torch.cuda.device(W.device):
+        rc = load_library().pcmm_plan_create(
+            ctypes.byref(out), M, K, int(Ncols), L, ctypes.cast(arr, ctypes.c_void_p), int(prime_bits), w_bits,
+            W.data_ptr(), W.device.index, _stream_handle(stream),
+        )
+    if rc != PCMM_OK:
+        raise PcmmError(rc, "pcmm_plan_create")
+    return PcmmPlan(out.value, M, K, int(Ncols), L, W.device.index)
+
+
+def pcmm_plan_workspace_bytes(plan: PcmmPlan) -> int:
+    return int(load_library().pcmm_plan_workspace_bytes(plan.handle))
+
+
+def pcmm_plan_digits(plan: PcmmPlan) -> int:
+    return int(load_library().pcmm_plan_digits(plan.handle))
+
+
+def _check_io(plan: PcmmPlan, A: torch.Tensor, C: torch.Tensor) -> None:
+    if plan.handle is None:
+        raise ValueError("plan was destroyed")
+    for name, t, rows in (("A", A, plan.K), ("C", C, plan.M)):
+        if not t.is_cuda or t.device.index != plan.device or not t.is_contiguous():
+            raise ValueError("%s must be a contiguous tensor on the plan's device" % name)
+        if t.dtype not in (torch.int64, torch.uint64) or tuple(t.shape) != (plan.L, rows, plan.Ncols):
+            raise ValueError("%s must be 64-bit integers of shape [L][%d][Ncols]" % (name, rows))
+
+
+def pcmm_run(plan: PcmmPlan, A: torch.Tensor, C: torch.Tensor, stream=None) -> None:
+    """Enqueue C[j] = W . A[j] mod q_j on `stream` (default: torch's current stream). Asynchronous."""
+    _check_io(plan, A, C)
+    with torch.cuda.device(plan.device):
+        rc = load_library().pcmm_run(plan.handle, A.data_ptr(), C.data_ptr(), _stream_handle(stream))
+    if rc != PCMM_OK:
+        raise PcmmError(rc, "pcmm_run")
+
+
+def pcmm_run_profiled(plan: PcmmPlan, A: torch.Tensor, C: torch.Tensor, stream=None):
+    """pcmm_run with per-kernel HIP-event timing; returns (ms_split, ms_gemm) after synchronising."""
+    _check_io(plan, A, C)
+    ms = (ctypes.c_float * 2)()
+    with torch.cuda.device(plan.device):
+        rc = load_library().pcmm_run_profiled(plan.handle, A.data_ptr(), C.data_ptr(), _stream_handle(stream), ms)
+    if rc != PCMM_OK:
+        raise PcmmError(rc, "pcmm_run_profiled")
+    return float(ms[0]), float(ms[1])
+
+
+def pcmm_plan_destroy(plan: PcmmPlan) -> None:
+    plan.destroy()
