@@ -17,6 +17,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <new>
+#include <type_traits>
 #include "../../include/pcmm.h"
 
 namespace {
@@ -53,6 +54,20 @@ __device__ __forceinline__ uint64_t mulmod_shoup(uint64_t x, uint64_t c, uint64_
     uint64_t qhat = __umul64hi(x, cs);
     uint64_t r = x * c - qhat * q;
     return r >= q ? r - q : r;
+}
+
+// acc += A x B on one 16 x 16 x 64 int8 tile.  Written as asm so that the accumulators are pinned to
+// the accumulation registers (AGPRs) for the whole kernel; the compiler's register allocator
+// otherwise keeps migrating 160+ accumulator registers between the two register files inside the
+// main loop.  The MFMA's result must not be read by a non-MFMA instruction for up to 18 cycles after
+// issue: readers use mfma_drain() first.
+__device__ __forceinline__ void mfma_i8(v4i &acc, const v4i &a, const v4i &b)
+{
+    asm volatile("v_mfma_i32_16x16x64_i8 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_drain()
+{
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -172,17 +187,21 @@ struct GemmArgs {
 // Each wave owns MT*16 rows and keeps E = D+S-1 int32 accumulators per output: accumulator e sums
 // the products W_slice_s x digit_d with s + d = e, which all carry the weight 256^e.
 // W fragments go global -> registers (each wave reads only its own rows); digit fragments are shared
-// by all waves and staged through LDS, double-buffered, one barrier per k-step of 64.
-template <int WM, int MT, int NT, int D, int S, bool SINGLE>
+// by all waves and staged through LDS.
+//
+// PIPE = true  (needs nkb % 4 == 0): deep software pipeline, see below.
+// PIPE = false (needs nkb % 2 == 0): two LDS buffers, loads one k-step ahead; for short contractions.
+template <int WM, int MT, int NT, int D, int S, bool SINGLE, bool PIPE>
 __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
 {
     constexpr int E = D + S - 1;
     constexpr int T = WM * 64;
     constexpr int CH = NT * D * kFrag;            // bytes of one digit chunk (one k-step)
     constexpr int UNITS = CH / 16;                // 16-byte units per chunk
-    constexpr int NLD = (UNITS + T - 1) / T;      // units per thread
+    constexpr int NLD = (UNITS + T - 1) / T;      // units per thread (the last ones clamped: duplicates)
+    static_assert(NT == 2, "a k-step is processed as two 16-column halves");
 
-    __shared__ __attribute__((aligned(16))) int8_t lds[2][CH];
+    __shared__ __attribute__((aligned(16))) int8_t lds[PIPE ? 3 : 2][CH];
 
     // ---- which tile: XCD-aware raster.  Work-groups are dealt round-robin to the 8 XCDs, so
     // bid % 8 names the XCD; each XCD walks its own contiguous range of tiles, m fastest inside
@@ -203,11 +222,18 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int nkb = a.nkb;
+    const int last = nkb - 1;
 
     const int8_t *Adc = a.Ad + (((int64_t)limb * a.ntiles + tn) * nkb) * CH;
     const int64_t mb0 = ((int64_t)tm * WM + wave) * MT;       // first 16-row block of this wave
     const int8_t *Wpc = a.Wp + (mb0 * nkb) * kFrag + lane * 16;
     const int64_t w_slice_stride = a.MB * nkb * kFrag;
+
+    // byte offsets of this thread's 16-byte units inside a chunk (same in global memory and in LDS);
+    // units past the end are clamped to the last one, which is then loaded and stored twice
+    int uoff[NLD];
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) uoff[i] = min((int)threadIdx.x + i * T, UNITS - 1) * 16;
 
     v4i acc[MT][NT][E];
 #pragma unroll
@@ -217,71 +243,129 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
 #pragma unroll
             for (int e = 0; e < E; ++e) acc[i][j][e] = (v4i){0, 0, 0, 0};
 
-    v4i wcur[S][MT], wnext[S][MT];
-    v4i stage[NLD];
+    constexpr int RW = PIPE ? 4 : 2;
+    v4i wreg[RW][S][MT];
+    v4i areg[RW][NLD];
+    v4i b0[D], b1[D];
 
-    // prologue: chunk 0 -> LDS buffer 0, W fragments of k-step 0 -> registers
+    auto load_w = [&](auto slot, int kb) {
+        constexpr int SL = decltype(slot)::value;
+        const int kk = min(kb, last);
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-        int u = threadIdx.x + i * T;
-        if (u < UNITS) stage[i] = *reinterpret_cast<const v4i *>(Adc + (int64_t)u * 16);
-    }
+        for (int s = 0; s < S; ++s)
 #pragma unroll
-    for (int s = 0; s < S; ++s)
+            for (int i = 0; i < MT; ++i)
+                wreg[SL][s][i] = *reinterpret_cast<const v4i *>(Wpc + s * w_slice_stride +
+                                                                ((int64_t)i * nkb + kk) * kFrag);
+    };
+    auto load_a = [&](auto slot, int kb) {
+        constexpr int SL = decltype(slot)::value;
+        const int8_t *src = Adc + (int64_t)min(kb, last) * CH;
 #pragma unroll
-        for (int i = 0; i < MT; ++i)
-            wcur[s][i] = *reinterpret_cast<const v4i *>(Wpc + s * w_slice_stride + ((int64_t)i * nkb) * kFrag);
+        for (int i = 0; i < NLD; ++i) areg[SL][i] = *reinterpret_cast<const v4i *>(src + uoff[i]);
+    };
+    auto store_a = [&](auto slot, int buf) {
+        constexpr int SL = decltype(slot)::value;
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-        int u = threadIdx.x + i * T;
-        if (u < UNITS) *reinterpret_cast<v4i *>(&lds[0][u * 16]) = stage[i];
-    }
-    __syncthreads();
-
-    for (int kb = 0; kb < nkb; ++kb) {
-        const int cur = kb & 1;
-        const bool more = kb + 1 < nkb;
-        if (more) {
-            const int8_t *src = Adc + (int64_t)(kb + 1) * CH;
+        for (int i = 0; i < NLD; ++i) *reinterpret_cast<v4i *>(&lds[buf][uoff[i]]) = areg[SL][i];
+    };
+    auto read_b = [&](v4i(&b)[D], int buf, int j) {
 #pragma unroll
-            for (int i = 0; i < NLD; ++i) {
-                int u = threadIdx.x + i * T;
-                if (u < UNITS) stage[i] = *reinterpret_cast<const v4i *>(src + (int64_t)u * 16);
-            }
+        for (int d = 0; d < D; ++d) b[d] = *reinterpret_cast<const v4i *>(&lds[buf][(j * D + d) * kFrag + lane * 16]);
+    };
+    auto mfma_block = [&](auto slot, v4i(&b)[D], auto jc) {
+        constexpr int SL = decltype(slot)::value;
+        constexpr int J = decltype(jc)::value;
+#pragma unroll
+        for (int d = 0; d < D; ++d)
 #pragma unroll
             for (int s = 0; s < S; ++s)
 #pragma unroll
                 for (int i = 0; i < MT; ++i)
-                    wnext[s][i] = *reinterpret_cast<const v4i *>(Wpc + s * w_slice_stride +
-                                                                 ((int64_t)i * nkb + kb + 1) * kFrag);
-        }
+                    mfma_i8(acc[i][J][d + s], wreg[SL][s][i], b[d]);
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    using I3 = std::integral_constant<int, 3>;
 
-#pragma unroll
-        for (int j = 0; j < NT; ++j) {
-#pragma unroll
-            for (int d = 0; d < D; ++d) {
-                v4i b = *reinterpret_cast<const v4i *>(&lds[cur][(j * D + d) * kFrag + lane * 16]);
-#pragma unroll
-                for (int s = 0; s < S; ++s)
-#pragma unroll
-                    for (int i = 0; i < MT; ++i)
-                        acc[i][j][d + s] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wcur[s][i], b, acc[i][j][d + s], 0, 0, 0);
-            }
-        }
-
-        if (more) {
-#pragma unroll
-            for (int i = 0; i < NLD; ++i) {
-                int u = threadIdx.x + i * T;
-                if (u < UNITS) *reinterpret_cast<v4i *>(&lds[cur ^ 1][u * 16]) = stage[i];
-            }
-#pragma unroll
-            for (int s = 0; s < S; ++s)
-#pragma unroll
-                for (int i = 0; i < MT; ++i) wcur[s][i] = wnext[s][i];
-        }
+    if constexpr (PIPE) {
+        // Software pipeline (one k-step = 64 k), all ring indices compile-time by unrolling 4 k-steps:
+        //   W fragments:    global -> wreg ring of 4, loaded 3 k-steps ahead of use
+        //   digit chunks:   global -> areg ring of 4, loaded 5 k-steps ahead, written to the LDS ring
+        //                   of 3 two k-steps ahead of use, one barrier per k-step
+        //   digit operands: LDS -> b0 / b1 (first / second 16-column block), each read half a k-step
+        //                   ahead of the MFMAs that consume it
+        // Loads past the last k-step are clamped to it (their data is never used).
+        load_a(I0{}, 0);
+        load_a(I1{}, 1);
+        load_w(I0{}, 0);
+        load_a(I2{}, 2);
+        load_w(I1{}, 1);
+        load_a(I3{}, 3);
+        load_w(I2{}, 2);
+        store_a(I0{}, 0);
+        store_a(I1{}, 1);
+        load_a(I0{}, 4);
         __syncthreads();
+        read_b(b0, 0, 0);
+
+        // One k-step with ring slot SL = kb % 4.  LDS buffer `buf` = kb % 3 is read, (kb+1) % 3 is read
+        // after the barrier, (kb+2) % 3 is written before it (its last readers finished before the
+        // previous barrier).
+        auto step = [&](auto slot, int kb, int buf) {
+            constexpr int SL = decltype(slot)::value;
+            const int nxt = buf == 2 ? 0 : buf + 1;
+            const int wr = nxt == 2 ? 0 : nxt + 1;
+            read_b(b1, buf, 1);
+            load_w(std::integral_constant<int, (SL + 3) & 3>{}, kb + 3);
+            load_a(std::integral_constant<int, (SL + 1) & 3>{}, kb + 5);
+            mfma_block(slot, b0, I0{});
+            store_a(std::integral_constant<int, (SL + 2) & 3>{}, wr);
+            __syncthreads();
+            read_b(b0, nxt, 0);
+            mfma_block(slot, b1, I1{});
+            return nxt;
+        };
+        int buf = 0;
+        for (int kb = 0; kb < nkb; kb += 4) {
+            buf = step(I0{}, kb, buf);
+            buf = step(I1{}, kb + 1, buf);
+            buf = step(I2{}, kb + 2, buf);
+            buf = step(I3{}, kb + 3, buf);
+        }
+    } else {
+        load_a(I0{}, 0);
+        load_w(I0{}, 0);
+        store_a(I0{}, 0);
+        __syncthreads();
+        auto step = [&](auto slot, int kb) {
+            constexpr int SL = decltype(slot)::value;
+            using NX = std::integral_constant<int, SL ^ 1>;
+            read_b(b0, SL, 0);
+            read_b(b1, SL, 1);
+            load_a(NX{}, kb + 1);
+            load_w(NX{}, kb + 1);
+            mfma_block(slot, b0, I0{});
+            mfma_block(slot, b1, I1{});
+            store_a(NX{}, SL ^ 1);
+            __syncthreads();
+        };
+        for (int kb = 0; kb < nkb; kb += 2) {   // nkb is even
+            step(I0{}, kb);
+            step(I1{}, kb + 1);
+        }
     }
+
+    // the drain must sit between the last MFMA and the first read of an accumulator: volatile asm
+    // statements keep their order, and the empty ones make every later read depend on them
+    mfma_drain();
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int e = 0; e < E; ++e) asm volatile("" : "+a"(acc[i][j][e]));
 
     // ---- epilogue.  Accumulator register r of lane l is output row 4*(l/16)+r, column l%16 of its
     // 16 x 16 block.  value = sum_e acc_e 256^e = vlo + 2^32 vhi with vlo, vhi of magnitude < 2^56.
@@ -329,6 +413,7 @@ struct pcmm_plan {
     int D, S;
     int WM, MT, NT;          // tile configuration
     bool single;             // one Barrett per output suffices
+    bool pipe;               // deep-pipelined main loop (K padded to a multiple of 256)
     int64_t MB, nkb, mtiles, ntiles;
     int8_t *Wp;              // device
     int8_t *Ad;              // device digit scratch
@@ -364,10 +449,14 @@ constexpr int tile_mt(int E) { return E <= 5 ? 4 : 2; }
 template <int WM, int MT, int NT, int D, int S>
 hipError_t launch_gemm_ds(const pcmm_plan *p, const GemmArgs &ga, int64_t grid, hipStream_t st)
 {
-    if (p->single)
-        hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, true>), dim3((unsigned)grid), dim3(WM * 64), 0, st, ga);
-    else
-        hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, false>), dim3((unsigned)grid), dim3(WM * 64), 0, st, ga);
+    const dim3 g((unsigned)grid), b(WM * 64);
+    if (p->pipe) {
+        if (p->single) hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, true, true>), g, b, 0, st, ga);
+        else hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, false, true>), g, b, 0, st, ga);
+    } else {
+        if (p->single) hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, true, false>), g, b, 0, st, ga);
+        else hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, false, false>), g, b, 0, st, ga);
+    }
     return hipGetLastError();
 }
 
@@ -529,7 +618,9 @@ pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncol
     p->mtiles = (M + BM - 1) / BM;
     p->ntiles = (Ncols + BN - 1) / BN;
     p->MB = p->mtiles * BM / 16;
-    p->nkb = (K + 63) / 64;
+    // long contractions: pad K to 4 k-steps so that the pipelined loop applies; short ones to 2
+    p->pipe = K >= 512;
+    p->nkb = p->pipe ? (K + 255) / 256 * 4 : (K + 127) / 128 * 2;
 
     // can value = sum_e acc_e 256^e be reduced in one go?  |acc_e| <= K * sum_{s+d=e} 128 * dmax_d,
     // dmax_d = 128 except for the top digit, which is at most top = ((qmax-1+Bias) >> 8(D-1)) - 128.
