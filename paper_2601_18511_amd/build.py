@@ -16,6 +16,8 @@ HIPCC_FLAGS = [
     "-fPIC",
     "-shared",
     "-Wall",
+    # the epilogue relies on exactly the double-precision operations it spells out
+    "-ffp-contract=off",
     # hipcc -O3 may otherwise fuse float code into packed-fp32 forms; keep them off for all device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]

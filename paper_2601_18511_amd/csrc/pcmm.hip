@@ -18,6 +18,7 @@
 #include <stdint.h>
 #include <new>
 #include <type_traits>
+#include <utility>
 #include "../../include/pcmm.h"
 
 namespace {
@@ -34,6 +35,15 @@ struct LimbConst {
     uint64_t off;    // q * floor(2^62 / q): added to a signed value of magnitude < 2^62 to make it positive
     uint64_t c32;    // 2^32 mod q
     uint64_t c32s;   // floor(c32 * 2^64 / q)  (Shoup companion of c32)
+    double qd;       // q as a double (exact for q < 2^53)
+    double invq;     // 1.0 / q, rounded to nearest
+};
+
+// How the epilogue reduces sum_e acc_e 256^e modulo q.
+enum Epi : int {
+    EPI_F64 = 0,     // q < 2^50: exact double-precision arithmetic (fma remainders), no 64-bit multiplies
+    EPI_INT1 = 1,    // any q < 2^62, value known to fit 62 bits: one 64-bit Barrett
+    EPI_INT2 = 2     // any q < 2^62: two Barretts and one Shoup multiplication by 2^32
 };
 
 // ------------------------------------------------------------------------------------------------
@@ -56,18 +66,95 @@ __device__ __forceinline__ uint64_t mulmod_shoup(uint64_t x, uint64_t c, uint64_
     return r >= q ? r - q : r;
 }
 
-// acc += A x B on one 16 x 16 x 64 int8 tile.  Written as asm so that the accumulators are pinned to
-// the accumulation registers (AGPRs) for the whole kernel; the compiler's register allocator
-// otherwise keeps migrating 160+ accumulator registers between the two register files inside the
-// main loop.  The MFMA's result must not be read by a non-MFMA instruction for up to 18 cycles after
-// issue: readers use mfma_drain() first.
-__device__ __forceinline__ void mfma_i8(v4i &acc, const v4i &a, const v4i &b)
+// The MFMA accumulators live in fixed accumulation registers a[0 : 4*MT*NT*E) that only the asm
+// statements below name; the compiler never sees them as values, so it can neither migrate them
+// between register files nor copy them at a point where the hardware would return a stale value.
+// (An MFMA result may not be read by a non-MFMA instruction for up to 18 cycles after issue, and the
+// hardware does not interlock; mfma_drain() provides the wait.)  Compiler-generated code never
+// allocates accumulation registers in these kernels: they are used only when the 256 ordinary
+// registers run out, and tests/test_build_asm.py checks that none appears outside the asm.
+//
+// acc[BASE : BASE+4) += A x B on one 16 x 16 x 64 int8 tile
+template <int BASE>
+__device__ __forceinline__ void mfma_i8(const v4i &a, const v4i &b)
 {
-    asm volatile("v_mfma_i32_16x16x64_i8 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+    asm volatile("v_mfma_i32_16x16x64_i8 a[%0:%1], %2, %3, a[%0:%1]" ::"n"(BASE), "n"(BASE + 3), "v"(a), "v"(b));
 }
+template <int IDX>
+__device__ __forceinline__ void acc_zero()
+{
+    asm volatile("v_accvgpr_write_b32 a[%0], 0" ::"n"(IDX));
+}
+template <int IDX>
+__device__ __forceinline__ int acc_read()
+{
+    int x;
+    asm volatile("v_accvgpr_read_b32 %0, a[%1]" : "=v"(x) : "n"(IDX));
+    return x;
+}
+// tells the compiler which accumulation registers the kernel uses (it sizes the register file from this)
+template <int NACC>
+__device__ __forceinline__ void acc_declare()
+{
+    static_assert(NACC == 96 || NACC == 112 || NACC == 128 || NACC == 160, "add a clobber for this count");
+    if constexpr (NACC == 96) asm volatile("" ::: "a95");
+    if constexpr (NACC == 112) asm volatile("" ::: "a111");
+    if constexpr (NACC == 128) asm volatile("" ::: "a127");
+    if constexpr (NACC == 160) asm volatile("" ::: "a159");
+}
+
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), fully unrolled
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// wait states between the last MFMA (or accumulator write) and the next different kind of access
 __device__ __forceinline__ void mfma_drain()
 {
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+}
+
+// Exact reduction in double precision.  `t` holds E integers of magnitude < 2^31 (as doubles);
+// returns (sum_e t[e] 256^e) mod q in [0, q) for q < 2^50.
+//
+// The accumulators are grouped in threes from the bottom, c_g = t[3g] + 2^8 t[3g+1] + 2^16 t[3g+2]
+// (|c_g| < 2^47.01, exact).  Horner in base 2^24 from the top group: X = r 2^24 is exact (a power-of-
+// two scaling); qh = rint(X / q) is an integer below 2^53 that differs from X/q by a few units at
+// most; fma(-qh, q, X) returns X - qh q exactly, because the true value is an integer of magnitude
+// below 3q < 2^53.  Adding c_g (sum below 2^53, exact) and taking one more such remainder leaves
+// |r| <= q/2 (1 + 2^-20).  After the last group a negative r is lifted by q.  Every operation is
+// either exact or feeds a rint whose result is corrected by the exact fma, so the result is the
+// canonical residue bit for bit.
+template <int E>
+__device__ __forceinline__ uint64_t reduce_f64(const double (&t)[E], double q, double invq)
+{
+    constexpr int G = (E + 2) / 3;
+    double c[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        c[g] = t[3 * g];
+        if (3 * g + 1 < E) c[g] = __builtin_fma(t[3 * g + 1], 256.0, c[g]);
+        if (3 * g + 2 < E) c[g] = __builtin_fma(t[3 * g + 2], 65536.0, c[g]);
+    }
+    double r = c[G - 1];
+#pragma unroll
+    for (int g = G - 2; g >= 0; --g) {
+        const double X = r * 16777216.0;
+        r = __builtin_fma(-__builtin_rint(X * invq), q, X);
+        const double y = r + c[g];
+        r = __builtin_fma(-__builtin_rint(y * invq), q, y);
+    }
+    if (G == 1) r = __builtin_fma(-__builtin_rint(r * invq), q, r);
+    r = r < 0.0 ? r + q : r;
+    // r is an integer in [0, 2^52): adding 2^52 places it in the low mantissa bits
+    return (uint64_t)__double_as_longlong(r + 4503599627370496.0) & 0x000FFFFFFFFFFFFFull;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -189,9 +276,8 @@ struct GemmArgs {
 // W fragments go global -> registers (each wave reads only its own rows); digit fragments are shared
 // by all waves and staged through LDS.
 //
-// PIPE = true  (needs nkb % 4 == 0): deep software pipeline, see below.
-// PIPE = false (needs nkb % 2 == 0): two LDS buffers, loads one k-step ahead; for short contractions.
-template <int WM, int MT, int NT, int D, int S, bool SINGLE, bool PIPE>
+// nkb (k-steps) must be even.
+template <int WM, int MT, int NT, int D, int S, int EPI>
 __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
 {
     constexpr int E = D + S - 1;
@@ -201,7 +287,7 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
     constexpr int NLD = (UNITS + T - 1) / T;      // units per thread (the last ones clamped: duplicates)
     static_assert(NT == 2, "a k-step is processed as two 16-column halves");
 
-    __shared__ __attribute__((aligned(16))) int8_t lds[PIPE ? 3 : 2][CH];
+    __shared__ __attribute__((aligned(16))) int8_t lds[2][CH];
 
     // ---- which tile: XCD-aware raster.  Work-groups are dealt round-robin to the 8 XCDs, so
     // bid % 8 names the XCD; each XCD walks its own contiguous range of tiles, m fastest inside
@@ -235,171 +321,136 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
 #pragma unroll
     for (int i = 0; i < NLD; ++i) uoff[i] = min((int)threadIdx.x + i * T, UNITS - 1) * 16;
 
-    v4i acc[MT][NT][E];
-#pragma unroll
-    for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j)
-#pragma unroll
-            for (int e = 0; e < E; ++e) acc[i][j][e] = (v4i){0, 0, 0, 0};
+    // accumulator (i, j, e) = registers a[4*((i*NT + j)*E + e) ...+4)
+    constexpr int NACC = 4 * MT * NT * E;
+    acc_declare<NACC>();
+    static_for<NACC>([&](auto ic) { acc_zero<decltype(ic)::value>(); });
+    mfma_drain();
 
-    constexpr int RW = PIPE ? 4 : 2;
-    v4i wreg[RW][S][MT];
-    v4i areg[RW][NLD];
-    v4i b0[D], b1[D];
+    // Software pipeline, one k-step = 64 k, LDS double-buffered, one barrier per k-step:
+    //   W fragments   global -> wreg[2], loaded one k-step ahead of use
+    //   digit chunk   global -> areg (second half of k-step kb-1) -> LDS[(kb+1)&1] (first half of kb)
+    //   digit operand LDS -> b, read at the start of each 16-column half
+    // The kernel is sized to at most 256 registers per lane so that two work-groups share a CU:
+    // the second wave on each SIMD issues MFMAs while the first waits on LDS, memory or the barrier.
+    // Memory instructions are spread between the MFMAs, because a wave issues in order and a burst
+    // of LDS writes (about 64 B/clk per CU) would hold back the MFMAs queued behind it.
+    // Loads past the last k-step are clamped to it (their data is never used).
+    v4i wreg[2][S][MT];
+    v4i areg[NLD];
+    v4i b[D];
+    constexpr int CNT = D * S * MT;                  // MFMAs per half k-step
+    constexpr int NW = S * MT;                       // W fragments per k-step
 
-    auto load_w = [&](auto slot, int kb) {
-        constexpr int SL = decltype(slot)::value;
-        const int kk = min(kb, last);
+    // prologue
 #pragma unroll
-        for (int s = 0; s < S; ++s)
+    for (int i = 0; i < NLD; ++i) areg[i] = *reinterpret_cast<const v4i *>(Adc + uoff[i]);
 #pragma unroll
-            for (int i = 0; i < MT; ++i)
-                wreg[SL][s][i] = *reinterpret_cast<const v4i *>(Wpc + s * w_slice_stride +
-                                                                ((int64_t)i * nkb + kk) * kFrag);
-    };
-    auto load_a = [&](auto slot, int kb) {
-        constexpr int SL = decltype(slot)::value;
-        const int8_t *src = Adc + (int64_t)min(kb, last) * CH;
+    for (int f = 0; f < NW; ++f)
+        wreg[0][f / MT][f % MT] = *reinterpret_cast<const v4i *>(Wpc + (f / MT) * w_slice_stride +
+                                                                 ((int64_t)(f % MT) * nkb) * kFrag);
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) areg[SL][i] = *reinterpret_cast<const v4i *>(src + uoff[i]);
-    };
-    auto store_a = [&](auto slot, int buf) {
-        constexpr int SL = decltype(slot)::value;
+    for (int i = 0; i < NLD; ++i) *reinterpret_cast<v4i *>(&lds[0][uoff[i]]) = areg[i];
+    {
+        const int8_t *src = Adc + (int64_t)min(1, last) * CH;
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) *reinterpret_cast<v4i *>(&lds[buf][uoff[i]]) = areg[SL][i];
-    };
-    auto read_b = [&](v4i(&b)[D], int buf, int j) {
-#pragma unroll
-        for (int d = 0; d < D; ++d) b[d] = *reinterpret_cast<const v4i *>(&lds[buf][(j * D + d) * kFrag + lane * 16]);
-    };
-    auto mfma_block = [&](auto slot, v4i(&b)[D], auto jc) {
-        constexpr int SL = decltype(slot)::value;
-        constexpr int J = decltype(jc)::value;
-#pragma unroll
-        for (int d = 0; d < D; ++d)
-#pragma unroll
-            for (int s = 0; s < S; ++s)
-#pragma unroll
-                for (int i = 0; i < MT; ++i)
-                    mfma_i8(acc[i][J][d + s], wreg[SL][s][i], b[d]);
-    };
-    using I0 = std::integral_constant<int, 0>;
-    using I1 = std::integral_constant<int, 1>;
-    using I2 = std::integral_constant<int, 2>;
-    using I3 = std::integral_constant<int, 3>;
+        for (int i = 0; i < NLD; ++i) areg[i] = *reinterpret_cast<const v4i *>(src + uoff[i]);
+    }
+    __syncthreads();
 
-    if constexpr (PIPE) {
-        // Software pipeline (one k-step = 64 k), all ring indices compile-time by unrolling 4 k-steps:
-        //   W fragments:    global -> wreg ring of 4, loaded 3 k-steps ahead of use
-        //   digit chunks:   global -> areg ring of 4, loaded 5 k-steps ahead, written to the LDS ring
-        //                   of 3 two k-steps ahead of use, one barrier per k-step
-        //   digit operands: LDS -> b0 / b1 (first / second 16-column block), each read half a k-step
-        //                   ahead of the MFMAs that consume it
-        // Loads past the last k-step are clamped to it (their data is never used).
-        load_a(I0{}, 0);
-        load_a(I1{}, 1);
-        load_w(I0{}, 0);
-        load_a(I2{}, 2);
-        load_w(I1{}, 1);
-        load_a(I3{}, 3);
-        load_w(I2{}, 2);
-        store_a(I0{}, 0);
-        store_a(I1{}, 1);
-        load_a(I0{}, 4);
+    auto step = [&](auto phase, int kb) {
+        constexpr int CUR = decltype(phase)::value, NXT = CUR ^ 1;
+        const int kw = min(kb + 1, last);
+        const int8_t *asrc = Adc + (int64_t)min(kb + 2, last) * CH;
+#pragma unroll
+        for (int d = 0; d < D; ++d) b[d] = *reinterpret_cast<const v4i *>(&lds[CUR][d * kFrag + lane * 16]);
+        // first half: W loads of k-step kb+1 and LDS writes of chunk kb+1 between the MFMAs
+        static_for<CNT>([&](auto mc) {
+            constexpr int m = decltype(mc)::value;
+            constexpr int OPS = NW + NLD;
+            constexpr int n_lo = (m * OPS + CNT - 1) / CNT, n_hi = ((m + 1) * OPS + CNT - 1) / CNT;
+            static_for<n_hi - n_lo>([&](auto jc) {
+                constexpr int n = n_lo + decltype(jc)::value;
+                if constexpr (n < NW) {
+                    wreg[NXT][n / MT][n % MT] = *reinterpret_cast<const v4i *>(
+                        Wpc + (n / MT) * w_slice_stride + ((int64_t)(n % MT) * nkb + kw) * kFrag);
+                } else if constexpr (n < OPS) {
+                    *reinterpret_cast<v4i *>(&lds[NXT][uoff[n - NW]]) = areg[n - NW];
+                }
+            });
+            constexpr int d = m / NW, ws = (m / MT) % S, wi = m % MT;
+            mfma_i8<4 * ((wi * NT + 0) * E + d + ws)>(wreg[CUR][ws][wi], b[d]);
+        });
+#pragma unroll
+        for (int d = 0; d < D; ++d) b[d] = *reinterpret_cast<const v4i *>(&lds[CUR][(D + d) * kFrag + lane * 16]);
+        // second half: loads of digit chunk kb+2 between the MFMAs
+        static_for<CNT>([&](auto mc) {
+            constexpr int m = decltype(mc)::value;
+            constexpr int OPS = NLD;
+            constexpr int n_lo = (m * OPS + CNT - 1) / CNT, n_hi = ((m + 1) * OPS + CNT - 1) / CNT;
+            static_for<n_hi - n_lo>([&](auto jc) {
+                constexpr int n = n_lo + decltype(jc)::value;
+                if constexpr (n < OPS) areg[n] = *reinterpret_cast<const v4i *>(asrc + uoff[n]);
+            });
+            constexpr int d = m / NW, ws = (m / MT) % S, wi = m % MT;
+            mfma_i8<4 * ((wi * NT + 1) * E + d + ws)>(wreg[CUR][ws][wi], b[d]);
+        });
         __syncthreads();
-        read_b(b0, 0, 0);
-
-        // One k-step with ring slot SL = kb % 4.  LDS buffer `buf` = kb % 3 is read, (kb+1) % 3 is read
-        // after the barrier, (kb+2) % 3 is written before it (its last readers finished before the
-        // previous barrier).
-        auto step = [&](auto slot, int kb, int buf) {
-            constexpr int SL = decltype(slot)::value;
-            const int nxt = buf == 2 ? 0 : buf + 1;
-            const int wr = nxt == 2 ? 0 : nxt + 1;
-            read_b(b1, buf, 1);
-            load_w(std::integral_constant<int, (SL + 3) & 3>{}, kb + 3);
-            load_a(std::integral_constant<int, (SL + 1) & 3>{}, kb + 5);
-            mfma_block(slot, b0, I0{});
-            store_a(std::integral_constant<int, (SL + 2) & 3>{}, wr);
-            __syncthreads();
-            read_b(b0, nxt, 0);
-            mfma_block(slot, b1, I1{});
-            return nxt;
-        };
-        int buf = 0;
-        for (int kb = 0; kb < nkb; kb += 4) {
-            buf = step(I0{}, kb, buf);
-            buf = step(I1{}, kb + 1, buf);
-            buf = step(I2{}, kb + 2, buf);
-            buf = step(I3{}, kb + 3, buf);
-        }
-    } else {
-        load_a(I0{}, 0);
-        load_w(I0{}, 0);
-        store_a(I0{}, 0);
-        __syncthreads();
-        auto step = [&](auto slot, int kb) {
-            constexpr int SL = decltype(slot)::value;
-            using NX = std::integral_constant<int, SL ^ 1>;
-            read_b(b0, SL, 0);
-            read_b(b1, SL, 1);
-            load_a(NX{}, kb + 1);
-            load_w(NX{}, kb + 1);
-            mfma_block(slot, b0, I0{});
-            mfma_block(slot, b1, I1{});
-            store_a(NX{}, SL ^ 1);
-            __syncthreads();
-        };
-        for (int kb = 0; kb < nkb; kb += 2) {   // nkb is even
-            step(I0{}, kb);
-            step(I1{}, kb + 1);
-        }
+    };
+    for (int kb = 0; kb < nkb; kb += 2) {   // nkb is even
+        step(std::integral_constant<int, 0>{}, kb);
+        step(std::integral_constant<int, 1>{}, kb + 1);
     }
 
-    // the drain must sit between the last MFMA and the first read of an accumulator: volatile asm
-    // statements keep their order, and the empty ones make every later read depend on them
+    // volatile asm statements keep their order: last MFMA, drain, accumulator reads
     mfma_drain();
-#pragma unroll
-    for (int i = 0; i < MT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j)
-#pragma unroll
-            for (int e = 0; e < E; ++e) asm volatile("" : "+a"(acc[i][j][e]));
 
     // ---- epilogue.  Accumulator register r of lane l is output row 4*(l/16)+r, column l%16 of its
-    // 16 x 16 block.  value = sum_e acc_e 256^e = vlo + 2^32 vhi with vlo, vhi of magnitude < 2^56.
+    // 16 x 16 block.
     const LimbConst lc = a.lc[limb];
     uint64_t *Cl = a.C + (int64_t)limb * a.M * a.Ncols;
-#pragma unroll
-    for (int i = 0; i < MT; ++i) {
-#pragma unroll
-        for (int j = 0; j < NT; ++j) {
+    static_for<MT * NT>([&](auto ijc) {
+        constexpr int i = decltype(ijc)::value / NT, j = decltype(ijc)::value % NT;
+        // 16 x 16 blocks that lie wholly in the padding are skipped (wave-uniform)
+        if ((mb0 + i) * 16 < a.M && ((int64_t)tn * NT + j) * 16 < a.Ncols) {
             const int64_t n = ((int64_t)tn * NT + j) * 16 + (lane & 15);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
+            static_for<4>([&](auto rc) {
+                constexpr int r = decltype(rc)::value;
                 const int64_t m = (mb0 + i) * 16 + (lane >> 4) * 4 + r;
-                int64_t vlo = 0, vhi = 0;
-#pragma unroll
-                for (int e = 0; e < E; ++e) {
-                    int64_t v = (int64_t)acc[i][j][e][r];
-                    if (e < 4) vlo += v << (8 * e);
-                    else vhi += v << (8 * (e - 4));
-                }
+                int av[E];
+                static_for<E>([&](auto ec) {
+                    constexpr int e = decltype(ec)::value;
+                    av[e] = acc_read<4 * ((i * NT + j) * E + e) + r>();
+                });
                 uint64_t res;
-                if (SINGLE) {
-                    // plan guarantees |vlo + 2^32 vhi| < 2^62
-                    res = barrett_u64((uint64_t)(vlo + (vhi << 32)) + lc.off, lc.q, lc.mu);
+                if constexpr (EPI == EPI_F64) {
+                    double t[E];
+#pragma unroll
+                    for (int e = 0; e < E; ++e) t[e] = (double)av[e];
+                    res = reduce_f64<E>(t, lc.qd, lc.invq);
                 } else {
-                    uint64_t rlo = barrett_u64((uint64_t)vlo + lc.off, lc.q, lc.mu);
-                    uint64_t rhi = barrett_u64((uint64_t)vhi + lc.off, lc.q, lc.mu);
-                    res = rlo + mulmod_shoup(rhi, lc.c32, lc.c32s, lc.q);
-                    if (res >= lc.q) res -= lc.q;
+                    // value = vlo + 2^32 vhi with vlo, vhi of magnitude < 2^56
+                    int64_t vlo = 0, vhi = 0;
+#pragma unroll
+                    for (int e = 0; e < E; ++e) {
+                        int64_t v = (int64_t)av[e];
+                        if (e < 4) vlo += v << (8 * e);
+                        else vhi += v << (8 * (e - 4));
+                    }
+                    if constexpr (EPI == EPI_INT1) {
+                        // plan guarantees |vlo + 2^32 vhi| < 2^62
+                        res = barrett_u64((uint64_t)(vlo + (vhi << 32)) + lc.off, lc.q, lc.mu);
+                    } else {
+                        uint64_t rlo = barrett_u64((uint64_t)vlo + lc.off, lc.q, lc.mu);
+                        uint64_t rhi = barrett_u64((uint64_t)vhi + lc.off, lc.q, lc.mu);
+                        res = rlo + mulmod_shoup(rhi, lc.c32, lc.c32s, lc.q);
+                        if (res >= lc.q) res -= lc.q;
+                    }
                 }
                 if (m < a.M && n < a.Ncols) Cl[m * a.Ncols + n] = res;
-            }
+            });
         }
-    }
+    });
 }
 
 }  // namespace
@@ -412,8 +463,7 @@ struct pcmm_plan {
     int L, prime_bits, w_bits, device;
     int D, S;
     int WM, MT, NT;          // tile configuration
-    bool single;             // one Barrett per output suffices
-    bool pipe;               // deep-pipelined main loop (K padded to a multiple of 256)
+    int epi;                 // Epi: how the epilogue reduces
     int64_t MB, nkb, mtiles, ntiles;
     int8_t *Wp;              // device
     int8_t *Ad;              // device digit scratch
@@ -450,12 +500,16 @@ template <int WM, int MT, int NT, int D, int S>
 hipError_t launch_gemm_ds(const pcmm_plan *p, const GemmArgs &ga, int64_t grid, hipStream_t st)
 {
     const dim3 g((unsigned)grid), b(WM * 64);
-    if (p->pipe) {
-        if (p->single) hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, true, true>), g, b, 0, st, ga);
-        else hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, false, true>), g, b, 0, st, ga);
+    // 50-bit primes need at least 7 digits and 7-digit primes can be below 2^50: D <= 6 always takes
+    // the double-precision epilogue, D = 8 never does
+    if (p->epi == EPI_F64) {
+        if constexpr (D <= 7) hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, EPI_F64>), g, b, 0, st, ga);
+        else return hipErrorInvalidValue;
     } else {
-        if (p->single) hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, true, false>), g, b, 0, st, ga);
-        else hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, false, false>), g, b, 0, st, ga);
+        if constexpr (D >= 7) {
+            if (p->epi == EPI_INT1) hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, EPI_INT1>), g, b, 0, st, ga);
+            else hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, EPI_INT2>), g, b, 0, st, ga);
+        } else return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
@@ -583,7 +637,7 @@ pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncol
     if (M <= 0 || K <= 0 || Ncols <= 0 || L <= 0 || L > 64) return PCMM_EINVAL;
     if (M > (int64_t)1 << 24 || Ncols > (int64_t)1 << 30) return PCMM_EINVAL;
     if (w_bits != 8 && w_bits != 16) return PCMM_EINVAL;
-    if (prime_bits < 10 || prime_bits > 62) return PCMM_EINVAL;
+    if (prime_bits < 20 || prime_bits > 62) return PCMM_EINVAL;
     if (device < 0) return PCMM_EINVAL;
     uint64_t qmax = 0;
     for (int j = 0; j < L; ++j) {
@@ -618,9 +672,7 @@ pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncol
     p->mtiles = (M + BM - 1) / BM;
     p->ntiles = (Ncols + BN - 1) / BN;
     p->MB = p->mtiles * BM / 16;
-    // long contractions: pad K to 4 k-steps so that the pipelined loop applies; short ones to 2
-    p->pipe = K >= 512;
-    p->nkb = p->pipe ? (K + 255) / 256 * 4 : (K + 127) / 128 * 2;
+    p->nkb = (K + 127) / 128 * 2;   // the main loop takes two k-steps of 64 per round
 
     // can value = sum_e acc_e 256^e be reduced in one go?  |acc_e| <= K * sum_{s+d=e} 128 * dmax_d,
     // dmax_d = 128 except for the top digit, which is at most top = ((qmax-1+Bias) >> 8(D-1)) - 128.
@@ -639,7 +691,7 @@ pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncol
             }
             bound += be << (8 * e);
         }
-        p->single = bound < ((u128)1 << 62);
+        p->epi = qmax < ((uint64_t)1 << 50) ? EPI_F64 : (bound < ((u128)1 << 62) ? EPI_INT1 : EPI_INT2);
     }
 
     DevGuard dg(device);
@@ -667,6 +719,8 @@ pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncol
             h[j].off = q * (uint64_t)((((u128)1) << 62) / q);
             h[j].c32 = (uint64_t)((((u128)1) << 32) % q);
             h[j].c32s = (uint64_t)(((u128)h[j].c32 << 64) / q);
+            h[j].qd = (double)q;
+            h[j].invq = 1.0 / (double)q;
         }
         if (hipMemcpyAsync(p->lc, h, lc_bytes, hipMemcpyHostToDevice, st) != hipSuccess ||
             hipMemsetAsync(err_dev, 0, sizeof(int), st) != hipSuccess ||

@@ -60,6 +60,10 @@ def test_tiny_workload_bit_exact(gpu_device):
         (40, 300, 129, 62, 2, 8),         # 8 digits
         (33, 65, 100, 28, 2, 8),          # small primes: 4 digits
         (50, 64, 100, 44, 2, 16),         # 6 digits + 2 slices
+        (260, 1000, 70, 36, 2, 8),        # many k-steps, ragged K tail (K not a multiple of 128)
+        (64, 2049, 40, 50, 1, 16),        # odd K just past a k-step boundary
+        (70, 640, 33, 55, 1, 8),          # 7 digits above 2^50: integer epilogue
+        (40, 200, 50, 54, 2, 16),         # 7 digits, 2 slices, integer two-part epilogue
     ],
 )
 def test_random_shapes_bit_exact(gpu_device, M, K, Ncols, bits, L, wbits):
