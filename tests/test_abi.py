@@ -1,0 +1,66 @@
+"""The C-ABI library loads without a GPU, exports every symbol the header declares, and turns bad
+arguments into status codes (no compute calls here)."""
+import ctypes
+import os
+import re
+
+import paper_2601_18511_amd as pkg
+from paper_2601_18511_amd import pcmm as binding
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "pcmm.h")
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pcmm_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported_and_bound():
+    lib = pkg.load_library()
+    names = _declared_functions()
+    assert len(names) >= 7
+    for name in names:
+        assert getattr(lib, name) is not None, name
+        assert hasattr(pkg, name), "python binding lacks " + name
+    assert sorted(binding.EXPORTED) == names
+
+
+def test_status_strings():
+    for code in range(5):
+        assert pkg.pcmm_status_str(code).startswith("PCMM_")
+    assert "unknown" in pkg.pcmm_status_str(99)
+
+
+def test_argument_validation_needs_no_device():
+    lib = pkg.load_library()
+    out = ctypes.c_void_p(123)
+    q = (ctypes.c_uint64 * 1)(68719403009)
+    dummy = ctypes.c_void_p(0x1000)     # never dereferenced: validation fails first
+    qp = ctypes.cast(q, ctypes.c_void_p)
+
+    def create(M=4, K=4, N=4, L=1, primes=qp, bits=36, wbits=8, W=dummy, dev=0):
+        return lib.pcmm_plan_create(ctypes.byref(out), M, K, N, L, primes, bits, wbits, W, dev, None)
+
+    assert create(M=0) == binding.PCMM_EINVAL and out.value is None
+    assert create(K=-1) == binding.PCMM_EINVAL
+    assert create(L=0) == binding.PCMM_EINVAL
+    assert create(L=65) == binding.PCMM_EINVAL
+    assert create(primes=None) == binding.PCMM_EINVAL
+    assert create(W=None) == binding.PCMM_EINVAL
+    assert create(wbits=12) == binding.PCMM_EINVAL
+    assert create(bits=35) == binding.PCMM_EINVAL          # prime not of that size
+    assert create(bits=63) == binding.PCMM_EINVAL
+    assert create(dev=-1) == binding.PCMM_EINVAL
+    even = (ctypes.c_uint64 * 1)(68719403008)
+    assert create(primes=ctypes.cast(even, ctypes.c_void_p)) == binding.PCMM_EINVAL
+    assert create(K=131072) == binding.PCMM_EUNSUPPORTED   # int32 accumulator headroom
+    assert create(K=65536, wbits=16) == binding.PCMM_EUNSUPPORTED
+    big = (ctypes.c_uint64 * 1)((1 << 60) - 93)             # odd 60-bit number: 8 digits + 2 slices
+    assert create(primes=ctypes.cast(big, ctypes.c_void_p), bits=60, wbits=16) == binding.PCMM_EUNSUPPORTED
+    assert lib.pcmm_plan_create(None, 4, 4, 4, 1, qp, 36, 8, dummy, 0, None) == binding.PCMM_EINVAL
+    assert lib.pcmm_run(None, dummy, dummy, None) == binding.PCMM_EINVAL
+    assert lib.pcmm_run_profiled(None, dummy, dummy, None, None) == binding.PCMM_EINVAL
+    assert lib.pcmm_plan_workspace_bytes(None) == 0
+    assert lib.pcmm_plan_digits(None) == 0
+    lib.pcmm_plan_destroy(None)

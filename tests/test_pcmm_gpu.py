@@ -76,3 +76,146 @@ def test_random_shapes_bit_exact(gpu_device, M, K, Ncols, bits, L, wbits):
     got, _ = _run_gpu(W, A, primes, bits, gpu_device)
     want = pcmm_oracle(W, A, primes)
     assert (got == want).all(), int((got != want).sum())
+
+
+def _digit_pattern_residues(q, bits, K, Ncols, rng):
+    """Residues whose balanced base-256 digits sit at the extremes (+127 / -128 / 0 / -1 patterns)."""
+    pats = []
+    nbytes = (bits + 7) // 8
+    for byte in (0x7F, 0x80, 0xFF, 0x00, 0x81, 0x7E):
+        v = int.from_bytes(bytes([byte]) * nbytes, "little") & ((1 << bits) - 1)
+        while v >= q:
+            v >>= 1
+        pats.append(v)
+    pats += [0, 1, q - 1, q - 2, q // 2, q // 2 + 1, (1 << (bits - 1)) - 1, 1 << (bits - 1)]
+    idx = rng.integers(0, len(pats), size=(K, Ncols))
+    return np.array(pats, dtype=np.uint64)[idx]
+
+
+@pytest.mark.parametrize("bits,wbits,K", [(36, 8, 14336), (50, 16, 1024), (62, 8, 2048), (36, 8, 131071)])
+def test_adversarial_extremes_and_int32_headroom(gpu_device, bits, wbits, K):
+    """All-(-128) / all-127 weight rows against extreme digit patterns: the int32 accumulators reach
+    K * 2^14 (2^27.8 at K = 14336, 2^31 - 2^14 at the largest supported K)."""
+    from oracle import pcmm_oracle
+
+    rng = np.random.default_rng(bits * 7 + K)
+    primes = pi.ntt_primes(bits, 1 << 12, 2)
+    M, Ncols = 8, 48
+    if wbits == 8:
+        W = rng.integers(-128, 128, size=(M, K)).astype(np.int8)
+        W[0, :], W[1, :] = -128, 127
+    else:
+        W = rng.integers(-32768, 32640, size=(M, K)).astype(np.int16)
+        W[0, :], W[1, :] = -32768, 32639
+    W[2, :] = 0
+    A = np.stack([_digit_pattern_residues(q, bits, K, Ncols, rng) for q in primes])
+    A[:, :, 0] = np.array(primes, dtype=np.uint64)[:, None] - np.uint64(1)      # a column of q-1
+    A[:, :, 1] = 0
+    got, _ = _run_gpu(W, A, primes, bits, gpu_device)
+    want = pcmm_oracle(W, A, primes)
+    assert (got == want).all(), int((got != want).sum())
+    assert (got[:, 2, :] == 0).all() and (got[:, :, 1] == 0).all()
+
+
+def test_closed_forms_on_the_gpu(gpu_device):
+    rng = np.random.default_rng(3)
+    primes = pi.ntt_primes(36, 1 << 13, 2)
+    K, Ncols = 192, 100
+    A = _rand_A(rng, K, Ncols, primes)
+    eye = np.eye(K, dtype=np.int8)
+    got, _ = _run_gpu(eye, A, primes, 36, gpu_device)
+    assert (got == A).all()
+    got, _ = _run_gpu((-eye).astype(np.int8), A, primes, 36, gpu_device)
+    for j, q in enumerate(primes):
+        assert (got[j] == (np.uint64(q) - A[j]) % np.uint64(q)).all()
+    W = rng.integers(-128, 128, size=(70, K)).astype(np.int8)
+    ones = np.ones((2, K, Ncols), dtype=np.uint64)
+    got, _ = _run_gpu(W, ones, primes, 36, gpu_device)
+    for j, q in enumerate(primes):
+        want = np.array([int(r) % q for r in W.astype(np.int64).sum(axis=1)], dtype=np.uint64)
+        assert (got[j] == want[:, None]).all()
+
+
+def test_block_identity_on_the_gpu(gpu_device):
+    """B^(u) = sum_v W^(u,v) A^(v) mod q (Section 5.1): split K in 2 and M in 2, partial products on the GPU."""
+    rng = np.random.default_rng(5)
+    primes = pi.ntt_primes(36, 1 << 13, 2)
+    M, K, Ncols = 192, 640, 96
+    W = _rand_W(rng, M, K, 8)
+    A = _rand_A(rng, K, Ncols, primes)
+    full, _ = _run_gpu(W, A, primes, 36, gpu_device)
+    qs = np.array(primes, dtype=np.uint64)[:, None, None]
+    for u in range(2):
+        acc = np.zeros((2, M // 2, Ncols), dtype=np.uint64)
+        for v in range(2):
+            part, _ = _run_gpu(np.ascontiguousarray(W[u * 96:(u + 1) * 96, v * 320:(v + 1) * 320]),
+                               np.ascontiguousarray(A[:, v * 320:(v + 1) * 320, :]), primes, 36, gpu_device)
+            acc = (acc + part) % qs
+        assert (acc == full[:, u * 96:(u + 1) * 96, :]).all()
+
+
+def test_plan_reuse_and_two_plans_interleaved(gpu_device):
+    """One plan run on two different inputs, and a second plan in between: scratch is per plan."""
+    import torch
+
+    import paper_2601_18511_amd as pkg
+    from oracle import pcmm_oracle
+
+    rng = np.random.default_rng(8)
+    primes = pi.ntt_primes(36, 1 << 13, 2)
+    W1, W2 = _rand_W(rng, 100, 256, 8), _rand_W(rng, 60, 128, 8)
+    A1a, A1b, A2 = _rand_A(rng, 256, 300, primes), _rand_A(rng, 256, 300, primes), _rand_A(rng, 128, 40, primes)
+    p1 = pkg.pcmm_plan_create(torch.from_numpy(W1).to(gpu_device), primes, 36, 300)
+    p2 = pkg.pcmm_plan_create(torch.from_numpy(W2).to(gpu_device), primes, 36, 40)
+    assert pkg.pcmm_plan_workspace_bytes(p1) > 0
+
+    def run(plan, A, M):
+        A_dev = torch.from_numpy(A.view(np.int64)).to(gpu_device)
+        C_dev = torch.empty((2, M, A.shape[2]), dtype=torch.int64, device=gpu_device)
+        pkg.pcmm_run(plan, A_dev, C_dev)
+        torch.cuda.synchronize()
+        return C_dev.cpu().numpy().view(np.uint64)
+
+    r1a = run(p1, A1a, 100)
+    r2 = run(p2, A2, 60)
+    r1b = run(p1, A1b, 100)
+    ms = pkg.pcmm_run_profiled(p1, torch.from_numpy(A1a.view(np.int64)).to(gpu_device),
+                               torch.empty((2, 100, 300), dtype=torch.int64, device=gpu_device))
+    assert ms[0] > 0 and ms[1] > 0
+    assert (r1a == pcmm_oracle(W1, A1a, primes)).all()
+    assert (r1b == pcmm_oracle(W1, A1b, primes)).all()
+    assert (r2 == pcmm_oracle(W2, A2, primes)).all()
+    pkg.pcmm_plan_destroy(p1)
+    pkg.pcmm_plan_destroy(p2)
+
+
+def test_int16_out_of_range_and_bad_arguments_are_status_codes(gpu_device):
+    import torch
+
+    import paper_2601_18511_amd as pkg
+
+    primes = pi.ntt_primes(50, 1 << 12, 2)
+    W = np.zeros((4, 8), dtype=np.int16)
+    W[3, 7] = 32640                                   # high byte would be +128
+    with pytest.raises(pkg.PcmmError) as e:
+        pkg.pcmm_plan_create(torch.from_numpy(W).to(gpu_device), primes, 50, 16)
+    assert e.value.status == pkg.pcmm.PCMM_EINVAL
+    W[3, 7] = 32639
+    plan = pkg.pcmm_plan_create(torch.from_numpy(W).to(gpu_device), primes, 50, 16)
+    pkg.pcmm_plan_destroy(plan)
+    W8 = torch.zeros((4, 8), dtype=torch.int8, device=gpu_device)
+    for bad_primes, bits in (([primes[0] + 1], 50), ([primes[0]], 49), ([(1 << 50) + 1], 50)):
+        with pytest.raises(pkg.PcmmError) as e:
+            pkg.pcmm_plan_create(W8, bad_primes, bits, 16)
+        assert e.value.status == pkg.pcmm.PCMM_EINVAL
+    Wbig = torch.zeros((1, 131072), dtype=torch.int8, device=gpu_device)
+    with pytest.raises(pkg.PcmmError) as e:
+        pkg.pcmm_plan_create(Wbig, [primes[0]], 50, 16)
+    assert e.value.status == pkg.pcmm.PCMM_EUNSUPPORTED
+
+
+def test_gpu_input_generator_matches_host_generator(gpu_device):
+    wl = pi.Workload("g", 8, 96, 256, 2, 36, 8, seed=3)
+    ref = pi.gen_A(wl)
+    got = pi.gen_A_torch(wl, gpu_device).cpu().numpy().view(np.uint64)
+    assert (ref == got).all()
