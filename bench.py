@@ -79,6 +79,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="attn_proj")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -103,6 +105,13 @@ def main() -> int:
     C_dev = torch.empty((wl.L, wl.M, wl.Ncols), dtype=torch.int64, device=dev)
     plan = pkg.pcmm_plan_create(W_dev, wl.primes, wl.prime_bits, wl.Ncols)
     stream = torch.cuda.current_stream()
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 27, dtype=torch.int64, device=dev)      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         pkg.pcmm_run(plan, A_dev, C_dev, stream)
