@@ -24,6 +24,7 @@
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
 constexpr int kFrag = 1024;   // bytes of one 16 x 64 int8 MFMA operand fragment
 constexpr int kXcd = 8;       // accelerator complex dies, each with its own L2
@@ -306,20 +307,38 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
     const int tn = (int)(grp * a.gn + within % gcount);
 
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    // the wave index is the same in all lanes: say so, so that addresses derived from it stay in
+    // scalar registers and loads take the (scalar base + 32-bit lane offset) form
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nkb = a.nkb;
     const int last = nkb - 1;
 
     const int8_t *Adc = a.Ad + (((int64_t)limb * a.ntiles + tn) * nkb) * CH;
     const int64_t mb0 = ((int64_t)tm * WM + wave) * MT;       // first 16-row block of this wave
-    const int8_t *Wpc = a.Wp + (mb0 * nkb) * kFrag + lane * 16;
-    const int64_t w_slice_stride = a.MB * nkb * kFrag;
+    // Both operands are fetched with buffer loads: a scalar descriptor (base + size, out-of-range reads
+    // return 0), a scalar byte offset for the k-step and a 32-bit lane offset, so that no vector ALU
+    // work goes into addresses.  One descriptor per W slice covers exactly this wave's MT row blocks,
+    // one covers this tile's digit chunks.
+    const uint32_t loff = (uint32_t)lane * 16u;
+    __amdgpu_buffer_rsrc_t wrs[S];
+#pragma unroll
+    for (int sl = 0; sl < S; ++sl)
+        wrs[sl] = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<int8_t *>(a.Wp + ((int64_t)sl * a.MB + mb0) * nkb * kFrag), 0, MT * nkb * kFrag, 0x00020000);
+    const __amdgpu_buffer_rsrc_t ars =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(Adc), 0, nkb * CH, 0x00020000);
+    auto ld_w = [&](int sl, int wi, int kk) -> v4i {   // fragment (slice sl, row block wi, k-step kk)
+        return (v4i)__builtin_amdgcn_raw_buffer_load_b128(wrs[sl], loff, (wi * nkb + kk) * kFrag, 0);
+    };
+    auto ld_a = [&](uint32_t unit_off, int kk) -> v4i {   // 16 bytes of digit chunk kk
+        return (v4i)__builtin_amdgcn_raw_buffer_load_b128(ars, unit_off, kk * CH, 0);
+    };
 
     // byte offsets of this thread's 16-byte units inside a chunk (same in global memory and in LDS);
     // units past the end are clamped to the last one, which is then loaded and stored twice
-    int uoff[NLD];
+    uint32_t uoff[NLD];
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) uoff[i] = min((int)threadIdx.x + i * T, UNITS - 1) * 16;
+    for (int i = 0; i < NLD; ++i) uoff[i] = (uint32_t)min((int)threadIdx.x + i * T, UNITS - 1) * 16u;
 
     // accumulator (i, j, e) = registers a[4*((i*NT + j)*E + e) ...+4)
     constexpr int NACC = 4 * MT * NT * E;
@@ -344,24 +363,19 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
 
     // prologue
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) areg[i] = *reinterpret_cast<const v4i *>(Adc + uoff[i]);
+    for (int i = 0; i < NLD; ++i) areg[i] = ld_a(uoff[i], 0);
 #pragma unroll
-    for (int f = 0; f < NW; ++f)
-        wreg[0][f / MT][f % MT] = *reinterpret_cast<const v4i *>(Wpc + (f / MT) * w_slice_stride +
-                                                                 ((int64_t)(f % MT) * nkb) * kFrag);
+    for (int f = 0; f < NW; ++f) wreg[0][f / MT][f % MT] = ld_w(f / MT, f % MT, 0);
 #pragma unroll
     for (int i = 0; i < NLD; ++i) *reinterpret_cast<v4i *>(&lds[0][uoff[i]]) = areg[i];
-    {
-        const int8_t *src = Adc + (int64_t)min(1, last) * CH;
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) areg[i] = *reinterpret_cast<const v4i *>(src + uoff[i]);
-    }
+    for (int i = 0; i < NLD; ++i) areg[i] = ld_a(uoff[i], min(1, last));
     __syncthreads();
 
     auto step = [&](auto phase, int kb) {
         constexpr int CUR = decltype(phase)::value, NXT = CUR ^ 1;
         const int kw = min(kb + 1, last);
-        const int8_t *asrc = Adc + (int64_t)min(kb + 2, last) * CH;
+        const int ka = min(kb + 2, last);
 #pragma unroll
         for (int d = 0; d < D; ++d) b[d] = *reinterpret_cast<const v4i *>(&lds[CUR][d * kFrag + lane * 16]);
         // first half: W loads of k-step kb+1 and LDS writes of chunk kb+1 between the MFMAs
@@ -372,8 +386,7 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
             static_for<n_hi - n_lo>([&](auto jc) {
                 constexpr int n = n_lo + decltype(jc)::value;
                 if constexpr (n < NW) {
-                    wreg[NXT][n / MT][n % MT] = *reinterpret_cast<const v4i *>(
-                        Wpc + (n / MT) * w_slice_stride + ((int64_t)(n % MT) * nkb + kw) * kFrag);
+                    wreg[NXT][n / MT][n % MT] = ld_w(n / MT, n % MT, kw);
                 } else if constexpr (n < OPS) {
                     *reinterpret_cast<v4i *>(&lds[NXT][uoff[n - NW]]) = areg[n - NW];
                 }
@@ -390,7 +403,7 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
             constexpr int n_lo = (m * OPS + CNT - 1) / CNT, n_hi = ((m + 1) * OPS + CNT - 1) / CNT;
             static_for<n_hi - n_lo>([&](auto jc) {
                 constexpr int n = n_lo + decltype(jc)::value;
-                if constexpr (n < OPS) areg[n] = *reinterpret_cast<const v4i *>(asrc + uoff[n]);
+                if constexpr (n < OPS) areg[n] = ld_a(uoff[n], ka);
             });
             constexpr int d = m / NW, ws = (m / MT) % S, wi = m % MT;
             mfma_i8<4 * ((wi * NT + 1) * E + d + ws)>(wreg[CUR][ws][wi], b[d]);
