@@ -60,7 +60,8 @@ typedef enum {
  *                synchronises that stream before returning
  *
  * PCMM_EUNSUPPORTED when: the int32 accumulators could overflow (needs (w_bits/8)*K <= 131071);
- * or digits + slices - 1 > 8 (e.g. int16 W with primes above 54 bits).
+ * or digits + slices - 1 > 8 (e.g. int16 W with primes above 54 bits); or one limb of digit planes
+ * (about K * Ncols * digits bytes) reaches 4 GiB, or one packed W slice 2 GiB.
  * PCMM_EINVAL for an int16 W entry above 32639, and for everything listed under PCMM_EINVAL above.
  */
 pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncols, int32_t L,

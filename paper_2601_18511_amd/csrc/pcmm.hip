@@ -161,7 +161,7 @@ __device__ __forceinline__ uint64_t reduce_f64(const double (&t)[E], double q, d
 // ------------------------------------------------------------------------------------------------
 // plan-time kernel: pack W
 // ------------------------------------------------------------------------------------------------
-// Output Wp[s][mb][kb][lane][16]: slice s of W[mb*16 + lane%16][kb*64 + (lane/16)*16 + 0..15],
+// Output Wp[s][kb][mb][lane][16]: slice s of W[mb*16 + lane%16][kb*64 + (lane/16)*16 + 0..15],
 // zero outside M x K.  int16 entries are split as w = lo + 256*hi with lo = sign-extended low byte;
 // err is set to 1 if some hi does not fit int8.
 template <typename WT, int S>
@@ -188,7 +188,7 @@ __global__ __launch_bounds__(256) void pack_w_kernel(const WT *__restrict__ W, i
         hi[j] = (int8_t)h;
         if (S == 2 && (h < -128 || h > 127)) atomicExch(err, 1);
     }
-    int8_t *dst = Wp + ((mb * nkb + kb) * 64 + lane) * 16;
+    int8_t *dst = Wp + ((kb * MB + mb) * 64 + lane) * 16;
 #pragma unroll
     for (int j = 0; j < 16; ++j) dst[j] = lo[j];
     if (S == 2) {
@@ -204,7 +204,7 @@ __global__ __launch_bounds__(256) void pack_w_kernel(const WT *__restrict__ W, i
 // Balanced base-256 digits: with Bias = sum_{i<D} 128 * 256^i, the bytes of x + Bias, each xor 0x80,
 // read as int8, are digits s_i in [-128,127] with x = sum_i s_i 256^i (valid while x + Bias < 256^D).
 //
-// Output layout Ad[limb][ntile][kb][nt][d][lane][16]; fragment (nt, d) of chunk (limb, ntile, kb)
+// Output layout Ad[limb][kb][ntile][nt][d][lane][16]; fragment (nt, d) of chunk (limb, kb, ntile)
 // holds digit d of A[limb][kb*64 + (lane/16)*16 + 0..15][(ntile*NT + nt)*16 + lane%16], zero outside
 // K x Ncols.  One block = 4 waves = 64 columns x 64 k; wave g takes k-group g, lane = column.
 template <int D>
@@ -242,7 +242,7 @@ __global__ __launch_bounds__(256) void split_kernel(const uint64_t *__restrict__
 
     const int64_t ntile = nb / NT;
     const int nt = (int)(nb % NT);
-    int8_t *chunk = Ad + ((limb * ntiles + ntile) * nkb + kb) * ((int64_t)NT * D * kFrag);
+    int8_t *chunk = Ad + ((limb * nkb + kb) * ntiles + ntile) * ((int64_t)NT * D * kFrag);
 #pragma unroll
     for (int d = 0; d < D; ++d) {
         v4i v;
@@ -258,8 +258,8 @@ __global__ __launch_bounds__(256) void split_kernel(const uint64_t *__restrict__
 // run-time kernel 2: int8 MFMA main loop + recombination + Barrett
 // ------------------------------------------------------------------------------------------------
 struct GemmArgs {
-    const int8_t *Wp;       // [S][MB][nkb][64][16]
-    const int8_t *Ad;       // [L][ntiles][nkb][NT][D][64][16]
+    const int8_t *Wp;       // [S][nkb][MB][64][16]
+    const int8_t *Ad;       // [L][nkb][ntiles][NT][D][64][16]
     uint64_t *C;            // [L][M][Ncols]
     const LimbConst *lc;    // [L]
     int64_t M, Ncols;
@@ -313,25 +313,30 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
     const int nkb = a.nkb;
     const int last = nkb - 1;
 
-    const int8_t *Adc = a.Ad + (((int64_t)limb * a.ntiles + tn) * nkb) * CH;
+    const int8_t *Adc = a.Ad + ((int64_t)limb * nkb * a.ntiles + tn) * CH;   // chunk 0 of this tile; k-step stride ntiles*CH
     const int64_t mb0 = ((int64_t)tm * WM + wave) * MT;       // first 16-row block of this wave
     // Both operands are fetched with buffer loads: a scalar descriptor (base + size, out-of-range reads
     // return 0), a scalar byte offset for the k-step and a 32-bit lane offset, so that no vector ALU
-    // work goes into addresses.  One descriptor per W slice covers exactly this wave's MT row blocks,
-    // one covers this tile's digit chunks.
+    // work goes into addresses.  One descriptor per W slice and one for this limb's digit chunks.
+    // Both arrays are k-step major, so that the work-groups running the same k-step at the same time read
+    // one contiguous region (spread over all L2 channels) rather than addresses a power of two apart.
     const uint32_t loff = (uint32_t)lane * 16u;
     __amdgpu_buffer_rsrc_t wrs[S];
 #pragma unroll
     for (int sl = 0; sl < S; ++sl)
         wrs[sl] = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<int8_t *>(a.Wp + ((int64_t)sl * a.MB + mb0) * nkb * kFrag), 0, MT * nkb * kFrag, 0x00020000);
+            const_cast<int8_t *>(a.Wp + ((int64_t)sl * nkb * a.MB + mb0) * kFrag), 0,
+            (uint32_t)((nkb * a.MB - mb0) * kFrag), 0x00020000);
     const __amdgpu_buffer_rsrc_t ars =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(Adc), 0, nkb * CH, 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(Adc), 0,
+                                          (uint32_t)(((int64_t)nkb * a.ntiles - tn) * CH), 0x00020000);
+    const int w_kstride = (int)a.MB * kFrag;              // bytes between k-steps of W
+    const int a_kstride = a.ntiles * CH;                  // bytes between k-steps of the digit chunks
     auto ld_w = [&](int sl, int wi, int kk) -> v4i {   // fragment (slice sl, row block wi, k-step kk)
-        return (v4i)__builtin_amdgcn_raw_buffer_load_b128(wrs[sl], loff, (wi * nkb + kk) * kFrag, 0);
+        return (v4i)__builtin_amdgcn_raw_buffer_load_b128(wrs[sl], loff, kk * w_kstride + wi * kFrag, 0);
     };
     auto ld_a = [&](uint32_t unit_off, int kk) -> v4i {   // 16 bytes of digit chunk kk
-        return (v4i)__builtin_amdgcn_raw_buffer_load_b128(ars, unit_off, kk * CH, 0);
+        return (v4i)__builtin_amdgcn_raw_buffer_load_b128(ars, unit_off, kk * a_kstride, 0);
     };
 
     // byte offsets of this thread's 16-byte units inside a chunk (same in global memory and in LDS);
@@ -713,6 +718,11 @@ pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncol
 
     const size_t wp_bytes = (size_t)S * p->MB * p->nkb * kFrag;
     const size_t ad_bytes = (size_t)L * p->ntiles * p->nkb * p->NT * D * kFrag;
+    // buffer loads address one W slice and one limb of digit planes with 32-bit offsets
+    if (wp_bytes / S >= ((size_t)1 << 31) || ad_bytes / L >= ((size_t)1 << 32)) {
+        delete p;
+        return PCMM_EUNSUPPORTED;
+    }
     const size_t lc_bytes = (size_t)L * sizeof(LimbConst);
     int *err_dev = nullptr;
     pcmm_status rc = PCMM_OK;
