@@ -48,10 +48,11 @@ typedef enum {
  *
  *   out          receives the plan (set to NULL on failure)
  *   M, K         W is M x K:  M output channels, K input channels (contraction length)
- *   Ncols        columns of every A_j and C_j (2N for ring degree N: both ciphertext components)
+ *   Ncols        columns of every A_j and C_j (2N for ring degree N: both ciphertext components),
+ *                at most 2^22; M at most 2^24
  *   L            number of RNS limbs, 1 <= L <= 64
  *   primes_host  [L] host array; each q_j odd with 2^(prime_bits-1) < q_j < 2^prime_bits
- *   prime_bits   size of the primes, 20 <= prime_bits <= 62
+ *   prime_bits   size of the primes, 24 <= prime_bits <= 62
  *   w_bits       8: W is int8_t [M][K];  16: W is int16_t [M][K] with every entry in [-32768, 32639]
  *                (so that its balanced high byte fits int8)
  *   W_dev        device pointer to W, row-major; read during this call only, not kept

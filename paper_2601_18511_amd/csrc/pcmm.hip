@@ -25,6 +25,7 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 
 constexpr int kFrag = 1024;   // bytes of one 16 x 64 int8 MFMA operand fragment
 constexpr int kXcd = 8;       // accelerator complex dies, each with its own L2
@@ -123,20 +124,25 @@ __device__ __forceinline__ void mfma_drain()
 }
 
 // Exact reduction in double precision.  `t` holds E integers of magnitude < 2^31 (as doubles);
-// returns (sum_e t[e] 256^e) mod q in [0, q) for q < 2^50.
+// returns (sum_e t[e] 256^e) mod q in [0, q) for 2^23 < q < 2^50.
 //
 // The accumulators are grouped in threes from the bottom, c_g = t[3g] + 2^8 t[3g+1] + 2^16 t[3g+2]
-// (|c_g| < 2^47.01, exact).  Horner in base 2^24 from the top group: X = r 2^24 is exact (a power-of-
-// two scaling); qh = rint(X / q) is an integer below 2^53 that differs from X/q by a few units at
-// most; fma(-qh, q, X) returns X - qh q exactly, because the true value is an integer of magnitude
-// below 3q < 2^53.  Adding c_g (sum below 2^53, exact) and taking one more such remainder leaves
-// |r| <= q/2 (1 + 2^-20).  After the last group a negative r is lifted by q.  Every operation is
-// either exact or feeds a rint whose result is corrected by the exact fma, so the result is the
+// (|c_g| < 2^47.01, exact).  Horner in base 2^24 from the top group, one step per group:
+//   X  = r 2^24                      exact (power-of-two scaling)
+//   qh = rint((X + c_g) / q)         the sum and the quotient are rounded: qh = (X + c_g)/q + eta with
+//                                    |eta| <= 0.5 + 3.01 * 2^-53 * |X + c_g|/q  <=  0.6
+//                                    (|X + c_g|/q < 2^48.01 in the first step, where r = c_top is not yet
+//                                    reduced, and < 2^24 afterwards)
+//   u  = fma(-qh, q, X)              = -c_g - eta q exactly: an integer of magnitude below 2^52
+//   r  = u + c_g                     = -eta q exactly, so |r| <= 0.6 q
+// After the last group a negative r is lifted by q, which lands in [0, q) because |r| <= 0.6 q.
+// Every operation is exact or feeds the rint whose error the exact fma absorbs, so the result is the
 // canonical residue bit for bit.
 template <int E>
 __device__ __forceinline__ uint64_t reduce_f64(const double (&t)[E], double q, double invq)
 {
     constexpr int G = (E + 2) / 3;
+    static_assert(G >= 2, "at least one Horner step");
     double c[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -148,11 +154,9 @@ __device__ __forceinline__ uint64_t reduce_f64(const double (&t)[E], double q, d
 #pragma unroll
     for (int g = G - 2; g >= 0; --g) {
         const double X = r * 16777216.0;
-        r = __builtin_fma(-__builtin_rint(X * invq), q, X);
-        const double y = r + c[g];
-        r = __builtin_fma(-__builtin_rint(y * invq), q, y);
+        const double qh = __builtin_rint((X + c[g]) * invq);
+        r = __builtin_fma(-qh, q, X) + c[g];
     }
-    if (G == 1) r = __builtin_fma(-__builtin_rint(r * invq), q, r);
     r = r < 0.0 ? r + q : r;
     // r is an integer in [0, 2^52): adding 2^52 places it in the low mantissa bits
     return (uint64_t)__double_as_longlong(r + 4503599627370496.0) & 0x000FFFFFFFFFFFFFull;
@@ -425,16 +429,26 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
 
     // ---- epilogue.  Accumulator register r of lane l is output row 4*(l/16)+r, column l%16 of its
     // 16 x 16 block.
+    // Stores go through a buffer descriptor that covers exactly the valid rows of the 16-row block:
+    // rows at or beyond M fall outside it and are dropped by the range check, and lanes whose column
+    // is at or beyond Ncols get an offset that is out of range for every row; no address arithmetic
+    // or branching per output.
     const LimbConst lc = a.lc[limb];
     uint64_t *Cl = a.C + (int64_t)limb * a.M * a.Ncols;
+    const uint32_t c_rowbytes = (uint32_t)a.Ncols * 8u;
     static_for<MT * NT>([&](auto ijc) {
         constexpr int i = decltype(ijc)::value / NT, j = decltype(ijc)::value % NT;
         // 16 x 16 blocks that lie wholly in the padding are skipped (wave-uniform)
         if ((mb0 + i) * 16 < a.M && ((int64_t)tn * NT + j) * 16 < a.Ncols) {
+            const int64_t m0 = (mb0 + i) * 16;
+            const uint32_t rows_valid = (uint32_t)min((int64_t)16, a.M - m0);
+            const __amdgpu_buffer_rsrc_t crs =
+                __builtin_amdgcn_make_buffer_rsrc(Cl + m0 * a.Ncols, 0, rows_valid * c_rowbytes, 0x00020000);
             const int64_t n = ((int64_t)tn * NT + j) * 16 + (lane & 15);
+            const uint32_t c_lane = n < a.Ncols ? (uint32_t)((lane >> 4) * 4) * c_rowbytes + (uint32_t)n * 8u
+                                                : 0x80000000u;
             static_for<4>([&](auto rc) {
                 constexpr int r = decltype(rc)::value;
-                const int64_t m = (mb0 + i) * 16 + (lane >> 4) * 4 + r;
                 int av[E];
                 static_for<E>([&](auto ec) {
                     constexpr int e = decltype(ec)::value;
@@ -465,7 +479,8 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
                         if (res >= lc.q) res -= lc.q;
                     }
                 }
-                if (m < a.M && n < a.Ncols) Cl[m * a.Ncols + n] = res;
+                __builtin_amdgcn_raw_buffer_store_b64((v2u){(uint32_t)res, (uint32_t)(res >> 32)}, crs,
+                                                      c_lane + (uint32_t)r * c_rowbytes, 0, 0);
             });
         }
     });
@@ -653,9 +668,9 @@ pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncol
     *out = nullptr;
     if (!primes_host || !W_dev) return PCMM_EINVAL;
     if (M <= 0 || K <= 0 || Ncols <= 0 || L <= 0 || L > 64) return PCMM_EINVAL;
-    if (M > (int64_t)1 << 24 || Ncols > (int64_t)1 << 30) return PCMM_EINVAL;
+    if (M > (int64_t)1 << 24 || Ncols > (int64_t)1 << 22) return PCMM_EINVAL;   // 32-bit row offsets in the stores
     if (w_bits != 8 && w_bits != 16) return PCMM_EINVAL;
-    if (prime_bits < 20 || prime_bits > 62) return PCMM_EINVAL;
+    if (prime_bits < 24 || prime_bits > 62) return PCMM_EINVAL;
     if (device < 0) return PCMM_EINVAL;
     uint64_t qmax = 0;
     for (int j = 0; j < L; ++j) {
