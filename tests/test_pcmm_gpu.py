@@ -64,6 +64,9 @@ def test_tiny_workload_bit_exact(gpu_device):
         (64, 2049, 40, 50, 1, 16),        # odd K just past a k-step boundary
         (70, 640, 33, 55, 1, 8),          # 7 digits above 2^50: integer epilogue
         (40, 200, 50, 54, 2, 16),         # 7 digits, 2 slices, integer two-part epilogue
+        (48, 192, 64, 24, 2, 16),         # smallest supported primes
+        (20, 128, 40, 49, 2, 8),          # just below 2^50: double-precision epilogue with 7 digits
+        (20, 128, 40, 51, 2, 8),          # just above: integer epilogue
     ],
 )
 def test_random_shapes_bit_exact(gpu_device, M, K, Ncols, bits, L, wbits):
@@ -92,7 +95,8 @@ def _digit_pattern_residues(q, bits, K, Ncols, rng):
     return np.array(pats, dtype=np.uint64)[idx]
 
 
-@pytest.mark.parametrize("bits,wbits,K", [(36, 8, 14336), (50, 16, 1024), (62, 8, 2048), (36, 8, 131071)])
+@pytest.mark.parametrize("bits,wbits,K", [(36, 8, 14336), (50, 16, 1024), (62, 8, 2048), (36, 8, 131071),
+                                          (50, 16, 65535), (24, 16, 65535)])
 def test_adversarial_extremes_and_int32_headroom(gpu_device, bits, wbits, K):
     """All-(-128) / all-127 weight rows against extreme digit patterns: the int32 accumulators reach
     K * 2^14 (2^27.8 at K = 14336, 2^31 - 2^14 at the largest supported K)."""
