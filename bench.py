@@ -176,6 +176,14 @@ def main() -> int:
             "split_frac_of_hbm_peak": split_alg_bytes / (split_avg * 1e-3) / 1e9 / HBM_PEAK_GBS,
         },
     }
+    # what the matrix cores alone sustain on this machine (no memory traffic): with random and with zero operands
+    probe_rand = pkg.pcmm_mfma_probe(0, 200000, True)
+    probe_zero = pkg.pcmm_mfma_probe(0, 200000, False)
+    result["mfma_probe"] = {
+        "random_operands": {"tops": probe_rand[0], "shader_mhz": probe_rand[1]},
+        "zero_operands": {"tops": probe_zero[0], "shader_mhz": probe_zero[1]},
+        "gemm_frac_of_random_operand_probe": gemm_tops / probe_rand[0],
+    }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, W_host, A_dev, C_dev)
     pkg.pcmm_plan_destroy(plan)

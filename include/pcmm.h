@@ -98,6 +98,18 @@ pcmm_status pcmm_run(const pcmm_plan *plan, const uint64_t *A_dev, uint64_t *C_d
 pcmm_status pcmm_run_profiled(const pcmm_plan *plan, const uint64_t *A_dev, uint64_t *C_dev,
                               void *stream, float *ms_out);
 
+/*
+ * Measurement aid: runs a register-resident loop of v_mfma_i32_16x16x64_i8 with no memory traffic on
+ * every CU of `device` (default stream, synchronous) and reports the sustained rate in TOP/s and the
+ * shader clock in MHz seen by the kernel.  random_operands != 0 fills the operand registers with
+ * pseudo-random bytes, 0 with zeros: the sustainable rate depends on data toggling.  This is the
+ * "MFMA-only peak on this box" that measured PCMM rates are compared with (the kernel design the paper
+ * leaves open is bounded by the matrix cores; Section 2.2 only says a GPU BLAS is used).
+ * iters: loop trips of 40 MFMAs per wave; 200000 runs for roughly 0.1 s.
+ */
+pcmm_status pcmm_mfma_probe(int32_t device, int32_t iters, int32_t random_operands, double *tops_out,
+                            double *shader_mhz_out);
+
 /* Frees everything the plan owns.  The caller makes sure no run of the plan is still in flight. */
 void pcmm_plan_destroy(pcmm_plan *plan);
 

@@ -7,6 +7,7 @@ from .pcmm import (  # noqa: F401
     PcmmError,
     PcmmPlan,
     load_library,
+    pcmm_mfma_probe,
     pcmm_plan_create,
     pcmm_plan_destroy,
     pcmm_plan_digits,

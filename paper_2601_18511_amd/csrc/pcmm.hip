@@ -486,6 +486,50 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
     });
 }
 
+// ------------------------------------------------------------------------------------------------
+// measurement: register-resident MFMA-only probe
+// ------------------------------------------------------------------------------------------------
+// 40 independent accumulators per wave (the footprint of the D = 5 main loop), four W-like and ten
+// digit-like operand registers, no memory traffic in the loop.  Operands are pseudo-random bytes or
+// zeros: the rate the matrix cores sustain depends on how much the data toggles (power).  One lane
+// also reports shader-clock and wall-clock ticks.
+__global__ __launch_bounds__(256) void mfma_probe_kernel(long long *out, int iters, int random_operands)
+{
+    const long long c0 = clock64(), w0 = wall_clock64();
+    unsigned x = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
+    v4i wa[4], bd[10];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            x ^= x << 13; x ^= x >> 17; x ^= x << 5;
+            wa[i][j] = random_operands ? (int)x : 0;
+        }
+#pragma unroll
+    for (int i = 0; i < 10; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            x ^= x << 13; x ^= x >> 17; x ^= x << 5;
+            bd[i][j] = random_operands ? (int)x : 0;
+        }
+    acc_declare<160>();
+    static_for<160>([&](auto ic) { acc_zero<decltype(ic)::value>(); });
+    mfma_drain();
+    for (int it = 0; it < iters; ++it)
+        static_for<40>([&](auto mc) {
+            constexpr int m = decltype(mc)::value;
+            mfma_i8<4 * m>(wa[m % 4], bd[m / 4]);
+        });
+    mfma_drain();
+    int sum = 0;
+    static_for<160>([&](auto ic) { sum += acc_read<decltype(ic)::value>(); });
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        out[0] = clock64() - c0;
+        out[1] = wall_clock64() - w0;
+        out[2] = sum;
+    }
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------------------------------------
@@ -819,6 +863,41 @@ pcmm_status pcmm_run_profiled(const pcmm_plan *plan, const uint64_t *A_dev, uint
 {
     if (!plan || !A_dev || !C_dev || !ms_out) return PCMM_EINVAL;
     return run_impl(plan, A_dev, C_dev, (hipStream_t)stream, ms_out);
+}
+
+pcmm_status pcmm_mfma_probe(int32_t device, int32_t iters, int32_t random_operands, double *tops_out,
+                            double *shader_mhz_out)
+{
+    if (device < 0 || iters <= 0 || !tops_out || !shader_mhz_out) return PCMM_EINVAL;
+    DevGuard dg(device);
+    if (!dg.ok) return PCMM_EDEVICE;
+    long long *dev = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    pcmm_status rc = PCMM_OK;
+    const int wgs = 512;   // two work-groups of four waves per CU on 256 CUs
+    float ms = 0.f;
+    long long h[3] = {0, 0, 0};
+    if (hipMalloc((void **)&dev, sizeof(h)) != hipSuccess) return PCMM_ENOMEM;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) rc = PCMM_EDEVICE;
+    if (rc == PCMM_OK) {
+        hipLaunchKernelGGL(mfma_probe_kernel, dim3(wgs), dim3(256), 0, nullptr, dev, 64, random_operands);   // warm-up
+        (void)hipEventRecord(e0, nullptr);
+        hipLaunchKernelGGL(mfma_probe_kernel, dim3(wgs), dim3(256), 0, nullptr, dev, iters, random_operands);
+        if (hipGetLastError() != hipSuccess || hipEventRecord(e1, nullptr) != hipSuccess ||
+            hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess ||
+            hipMemcpy(h, dev, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess)
+            rc = PCMM_EDEVICE;
+    }
+    if (rc == PCMM_OK && ms > 0.f && h[1] > 0) {
+        *tops_out = 2.0 * 16 * 16 * 64 * 40.0 * (double)iters * 4.0 * wgs / (ms * 1e-3) / 1e12;
+        *shader_mhz_out = (double)h[0] / (double)h[1] * 100.0;   // the wall clock ticks at 100 MHz
+    } else if (rc == PCMM_OK) {
+        rc = PCMM_EDEVICE;
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    (void)hipFree(dev);
+    return rc;
 }
 
 void pcmm_plan_destroy(pcmm_plan *plan)

@@ -22,6 +22,7 @@ EXPORTED = (
     "pcmm_run_profiled",
     "pcmm_plan_destroy",
     "pcmm_status_str",
+    "pcmm_mfma_probe",
 )
 
 _lib: Optional[ctypes.CDLL] = None
@@ -52,6 +53,8 @@ def load_library() -> ctypes.CDLL:
     lib.pcmm_run.restype = ctypes.c_int
     lib.pcmm_run_profiled.argtypes = [vp, vp, vp, vp, ctypes.POINTER(ctypes.c_float)]
     lib.pcmm_run_profiled.restype = ctypes.c_int
+    lib.pcmm_mfma_probe.argtypes = [i32, i32, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+    lib.pcmm_mfma_probe.restype = ctypes.c_int
     lib.pcmm_plan_destroy.argtypes = [vp]
     lib.pcmm_plan_destroy.restype = None
     lib.pcmm_status_str.argtypes = [ctypes.c_int]
@@ -144,6 +147,16 @@ def pcmm_run_profiled(plan: PcmmPlan, A: torch.Tensor, C: torch.Tensor, stream=N
     if rc != PCMM_OK:
         raise PcmmError(rc, "pcmm_run_profiled")
     return float(ms[0]), float(ms[1])
+
+
+def pcmm_mfma_probe(device: int = 0, iters: int = 200000, random_operands: bool = True):
+    """MFMA-only sustained rate on `device`: returns (TOP/s, shader clock in MHz). Synchronous."""
+    tops, mhz = ctypes.c_double(), ctypes.c_double()
+    rc = load_library().pcmm_mfma_probe(int(device), int(iters), 1 if random_operands else 0,
+                                        ctypes.byref(tops), ctypes.byref(mhz))
+    if rc != PCMM_OK:
+        raise PcmmError(rc, "pcmm_mfma_probe")
+    return float(tops.value), float(mhz.value)
 
 
 def pcmm_plan_destroy(plan: PcmmPlan) -> None:

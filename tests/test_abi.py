@@ -64,3 +64,7 @@ def test_argument_validation_needs_no_device():
     assert lib.pcmm_plan_workspace_bytes(None) == 0
     assert lib.pcmm_plan_digits(None) == 0
     lib.pcmm_plan_destroy(None)
+    tops, mhz = ctypes.c_double(), ctypes.c_double()
+    assert lib.pcmm_mfma_probe(-1, 10, 1, ctypes.byref(tops), ctypes.byref(mhz)) == binding.PCMM_EINVAL
+    assert lib.pcmm_mfma_probe(0, 0, 1, ctypes.byref(tops), ctypes.byref(mhz)) == binding.PCMM_EINVAL
+    assert lib.pcmm_mfma_probe(0, 10, 1, None, ctypes.byref(mhz)) == binding.PCMM_EINVAL

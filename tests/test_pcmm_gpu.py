@@ -223,3 +223,12 @@ def test_gpu_input_generator_matches_host_generator(gpu_device):
     ref = pi.gen_A(wl)
     got = pi.gen_A_torch(wl, gpu_device).cpu().numpy().view(np.uint64)
     assert (ref == got).all()
+
+
+def test_mfma_probe_reports_a_plausible_rate(gpu_device):
+    import paper_2601_18511_amd as pkg
+
+    tops, mhz = pkg.pcmm_mfma_probe(0, 20000, True)
+    assert 1000.0 < tops < 5200.0 and 500.0 < mhz < 2600.0
+    tops0, mhz0 = pkg.pcmm_mfma_probe(0, 20000, False)
+    assert tops0 >= 0.9 * tops
