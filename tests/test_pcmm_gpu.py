@@ -232,3 +232,38 @@ def test_mfma_probe_reports_a_plausible_rate(gpu_device):
     assert 1000.0 < tops < 5200.0 and 500.0 < mhz < 2600.0
     tops0, mhz0 = pkg.pcmm_mfma_probe(0, 20000, False)
     assert tops0 >= 0.9 * tops
+
+
+def test_pcmm_run_inside_a_hip_graph_replays_correctly(gpu_device):
+    """pcmm_run only enqueues kernels (no allocation, no memset, no synchronisation), so it can be
+    captured; every replay, with eager work and synchronisations in between, must match the oracle."""
+    import torch
+
+    import paper_2601_18511_amd as pkg
+    from oracle import pcmm_oracle
+
+    rng = np.random.default_rng(77)
+    primes = pi.ntt_primes(36, 1 << 13, 2)
+    W = _rand_W(rng, 130, 320, 8)
+    plan = pkg.pcmm_plan_create(torch.from_numpy(W).to(gpu_device), primes, 36, 200)
+    A_dev = torch.zeros((2, 320, 200), dtype=torch.int64, device=gpu_device)
+    C_dev = torch.zeros((2, 130, 200), dtype=torch.int64, device=gpu_device)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        pkg.pcmm_run(plan, A_dev, C_dev)          # warm-up outside capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        pkg.pcmm_run(plan, A_dev, C_dev)          # current stream is the capture stream here
+    for rep in range(3):
+        A = _rand_A(rng, 320, 200, primes)
+        A_dev.copy_(torch.from_numpy(A.view(np.int64)))
+        C_dev.fill_(-1)                            # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = C_dev.cpu().numpy().view(np.uint64)
+        assert (got == pcmm_oracle(W, A, primes)).all(), rep
+    pkg.pcmm_plan_destroy(plan)
