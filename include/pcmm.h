@@ -47,7 +47,8 @@ typedef enum {
  * step, Section 5.3: a layout-only transformation of the weights, done once).
  *
  *   out          receives the plan (set to NULL on failure)
- *   M, K         W is M x K:  M output channels, K input channels (contraction length)
+ *   M, K         W is M x K:  M output channels, K input channels (contraction length),
+ *                K at most 2^22 - 128
  *   Ncols        columns of every A_j and C_j (2N for ring degree N: both ciphertext components),
  *                at most 2^22; M at most 2^24
  *   L            number of RNS limbs, 1 <= L <= 64
@@ -60,9 +61,11 @@ typedef enum {
  *   stream       hipStream_t (NULL = default stream) used for the packing kernels; this call
  *                synchronises that stream before returning
  *
- * PCMM_EUNSUPPORTED when: the int32 accumulators could overflow (needs (w_bits/8)*K <= 131071);
- * or digits + slices - 1 > 8 (e.g. int16 W with primes above 54 bits); or one limb of digit planes
- * (about K * Ncols * digits bytes) reaches 4 GiB, or one packed W slice 2 GiB.
+ * PCMM_EUNSUPPORTED when: digits + slices - 1 > 8 (e.g. int16 W with primes above 54 bits); or one
+ * limb of digit planes (about K * Ncols * digits bytes) reaches 4 GiB, or one packed W slice 2 GiB.
+ * The int32 accumulators hold a contraction over (w_bits/8)*K <= 131071; a longer K is cut into
+ * ranges of 130944 (int8 W) or 65408 (int16 W) values of k, one MFMA kernel launch each, and every
+ * launch after the first adds its result to C modulo q_j (the result is the same, bit for bit).
  * PCMM_EINVAL for an int16 W entry above 32639, and for everything listed under PCMM_EINVAL above.
  */
 pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncols, int32_t L,
@@ -93,7 +96,7 @@ pcmm_status pcmm_run(const pcmm_plan *plan, const uint64_t *A_dev, uint64_t *C_d
 /*
  * Same as pcmm_run, but brackets each kernel with HIP events on `stream`, synchronises, and
  * reports the kernel durations in milliseconds: ms_out[0] = digit-split kernel, ms_out[1] =
- * MFMA + epilogue kernel.  ms_out is a host array of 2 floats.  For measurement harnesses.
+ * MFMA + epilogue kernel (all its launches together when K is cut into ranges).  ms_out is a host array of 2 floats.  For measurement harnesses.
  */
 pcmm_status pcmm_run_profiled(const pcmm_plan *plan, const uint64_t *A_dev, uint64_t *C_dev,
                               void *stream, float *ms_out);

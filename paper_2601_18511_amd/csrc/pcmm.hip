@@ -16,6 +16,7 @@
 // a wave fetches it with one 16-byte load per lane from contiguous memory.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <algorithm>
 #include <new>
 #include <type_traits>
 #include <utility>
@@ -268,7 +269,9 @@ struct GemmArgs {
     const LimbConst *lc;    // [L]
     int64_t M, Ncols;
     int64_t MB;             // padded M / 16
-    int nkb;                // padded K / 64
+    int nkb;                // padded K / 64: k-steps in the layouts of Wp and Ad
+    int kb0, nkbc;          // this launch contracts k-steps [kb0, kb0 + nkbc), nkbc even
+    int accumulate;         // 0: C = result;  1: C = (C + result) mod q  (later slices of a long K)
     int mtiles, ntiles, L;
     int gn;                 // n-tiles per raster group
     int64_t per_xcd;        // work items per XCD
@@ -281,7 +284,7 @@ struct GemmArgs {
 // W fragments go global -> registers (each wave reads only its own rows); digit fragments are shared
 // by all waves and staged through LDS.
 //
-// nkb (k-steps) must be even.
+// nkbc (k-steps of one launch) must be even.
 template <int WM, int MT, int NT, int D, int S, int EPI>
 __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
 {
@@ -314,10 +317,12 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
     // the wave index is the same in all lanes: say so, so that addresses derived from it stay in
     // scalar registers and loads take the (scalar base + 32-bit lane offset) form
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int nkb = a.nkb;
+    const int nkb = a.nkbc;                                   // k-steps of this launch, numbered from 0 below
     const int last = nkb - 1;
+    const int64_t kleft = a.nkb - a.kb0;                      // k-steps from kb0 to the end of the layouts
 
-    const int8_t *Adc = a.Ad + ((int64_t)limb * nkb * a.ntiles + tn) * CH;   // chunk 0 of this tile; k-step stride ntiles*CH
+    // chunk kb0 of this tile; k-step stride ntiles*CH
+    const int8_t *Adc = a.Ad + (((int64_t)limb * a.nkb + a.kb0) * a.ntiles + tn) * CH;
     const int64_t mb0 = ((int64_t)tm * WM + wave) * MT;       // first 16-row block of this wave
     // Both operands are fetched with buffer loads: a scalar descriptor (base + size, out-of-range reads
     // return 0), a scalar byte offset for the k-step and a 32-bit lane offset, so that no vector ALU
@@ -329,11 +334,11 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
 #pragma unroll
     for (int sl = 0; sl < S; ++sl)
         wrs[sl] = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<int8_t *>(a.Wp + ((int64_t)sl * nkb * a.MB + mb0) * kFrag), 0,
-            (uint32_t)((nkb * a.MB - mb0) * kFrag), 0x00020000);
+            const_cast<int8_t *>(a.Wp + (((int64_t)sl * a.nkb + a.kb0) * a.MB + mb0) * kFrag), 0,
+            (uint32_t)((kleft * a.MB - mb0) * kFrag), 0x00020000);
     const __amdgpu_buffer_rsrc_t ars =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(Adc), 0,
-                                          (uint32_t)(((int64_t)nkb * a.ntiles - tn) * CH), 0x00020000);
+                                          (uint32_t)((kleft * a.ntiles - tn) * CH), 0x00020000);
     const int w_kstride = (int)a.MB * kFrag;              // bytes between k-steps of W
     const int a_kstride = a.ntiles * CH;                  // bytes between k-steps of the digit chunks
     auto ld_w = [&](int sl, int wi, int kk) -> v4i {   // fragment (slice sl, row block wi, k-step kk)
@@ -436,6 +441,10 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
     const LimbConst lc = a.lc[limb];
     uint64_t *Cl = a.C + (int64_t)limb * a.M * a.Ncols;
     const uint32_t c_rowbytes = (uint32_t)a.Ncols * 8u;
+    // The whole epilogue exists twice, with and without the read-add of the previous contents of C,
+    // chosen once per wave: a branch per output would stop the scheduler from overlapping outputs.
+    auto epilogue = [&](auto accumulate_c) {
+    constexpr bool ACCUMULATE = decltype(accumulate_c)::value;
     static_for<MT * NT>([&](auto ijc) {
         constexpr int i = decltype(ijc)::value / NT, j = decltype(ijc)::value % NT;
         // 16 x 16 blocks that lie wholly in the padding are skipped (wave-uniform)
@@ -479,11 +488,19 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
                         if (res >= lc.q) res -= lc.q;
                     }
                 }
+                if constexpr (ACCUMULATE) {   // rows and columns outside C read as 0
+                    const v2u old = __builtin_amdgcn_raw_buffer_load_b64(crs, c_lane + (uint32_t)r * c_rowbytes, 0, 0);
+                    res += (uint64_t)old[0] | ((uint64_t)old[1] << 32);
+                    if (res >= lc.q) res -= lc.q;
+                }
                 __builtin_amdgcn_raw_buffer_store_b64((v2u){(uint32_t)res, (uint32_t)(res >> 32)}, crs,
                                                       c_lane + (uint32_t)r * c_rowbytes, 0, 0);
             });
         }
     });
+    };
+    if (a.accumulate) epilogue(std::true_type{});
+    else epilogue(std::false_type{});
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -542,6 +559,7 @@ struct pcmm_plan {
     int WM, MT, NT;          // tile configuration
     int epi;                 // Epi: how the epilogue reduces
     int64_t MB, nkb, mtiles, ntiles;
+    int64_t nkb_launch;      // most k-steps one GEMM launch may contract (int32 accumulator headroom)
     int8_t *Wp;              // device
     int8_t *Ad;              // device digit scratch
     LimbConst *lc;           // device
@@ -665,6 +683,9 @@ pcmm_status run_impl(const pcmm_plan *p, const uint64_t *A, uint64_t *C, hipStre
     ga.Ncols = p->Ncols;
     ga.MB = p->MB;
     ga.nkb = (int)p->nkb;
+    ga.kb0 = 0;
+    ga.nkbc = (int)p->nkb;
+    ga.accumulate = 0;
     ga.mtiles = (int)p->mtiles;
     ga.ntiles = (int)p->ntiles;
     ga.L = p->L;
@@ -678,7 +699,14 @@ pcmm_status run_impl(const pcmm_plan *p, const uint64_t *A, uint64_t *C, hipStre
     if (launch_split(p, A, st) != hipSuccess) return PCMM_EDEVICE;
     if (ms && (hipEventRecord(p->ev[1], st) != hipSuccess || hipEventRecord(p->ev[2], st) != hipSuccess))
         return PCMM_EDEVICE;
-    if (launch_gemm(p, ga, grid, st) != hipSuccess) return PCMM_EDEVICE;
+    // A contraction longer than the int32 accumulators can hold runs as several launches over
+    // consecutive ranges of k; every launch after the first adds its result to C modulo q_j.
+    for (int64_t kb0 = 0; kb0 < p->nkb; kb0 += p->nkb_launch) {
+        ga.kb0 = (int)kb0;
+        ga.nkbc = (int)std::min(p->nkb_launch, p->nkb - kb0);
+        ga.accumulate = kb0 > 0;
+        if (launch_gemm(p, ga, grid, st) != hipSuccess) return PCMM_EDEVICE;
+    }
     if (ms) {
         if (hipEventRecord(p->ev[3], st) != hipSuccess) return PCMM_EDEVICE;
         if (hipEventSynchronize(p->ev[3]) != hipSuccess) return PCMM_EDEVICE;
@@ -724,7 +752,11 @@ pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncol
         if (q > qmax) qmax = q;
     }
     const int S = w_bits / 8;
-    if ((int64_t)S * K > 131071) return PCMM_EUNSUPPORTED;   // int32 headroom: S*K*2^14 < 2^31
+    if (K > ((int64_t)1 << 22) - 128) return PCMM_EINVAL;   // k-steps are a grid dimension of the split kernel
+    // int32 headroom: one launch may contract Kl values of k with S*Kl*2^14 < 2^31, S*Kl <= 131071;
+    // in k-steps of 64, rounded down to the even count the main loop needs
+    const int64_t nkb_launch = 131071 / S / 128 * 2;
+    const int64_t K_launch = std::min(K, nkb_launch * 64);
 
     // smallest D with (qmax - 1) + Bias_D < 256^D
     int D = 0;
@@ -750,6 +782,7 @@ pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncol
     p->ntiles = (Ncols + BN - 1) / BN;
     p->MB = p->mtiles * BM / 16;
     p->nkb = (K + 127) / 128 * 2;   // the main loop takes two k-steps of 64 per round
+    p->nkb_launch = nkb_launch;
 
     // can value = sum_e acc_e 256^e be reduced in one go?  |acc_e| <= K * sum_{s+d=e} 128 * dmax_d,
     // dmax_d = 128 except for the top digit, which is at most top = ((qmax-1+Bias) >> 8(D-1)) - 128.
@@ -764,7 +797,7 @@ pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncol
             for (int s = 0; s < S; ++s) {
                 int d = e - s;
                 if (d < 0 || d >= D) continue;
-                be += (u128)K * 128 * (u128)(d == D - 1 ? top : 128);
+                be += (u128)K_launch * 128 * (u128)(d == D - 1 ? top : 128);
             }
             bound += be << (8 * e);
         }

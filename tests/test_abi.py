@@ -54,8 +54,9 @@ def test_argument_validation_needs_no_device():
     assert create(dev=-1) == binding.PCMM_EINVAL
     even = (ctypes.c_uint64 * 1)(68719403008)
     assert create(primes=ctypes.cast(even, ctypes.c_void_p)) == binding.PCMM_EINVAL
-    assert create(K=131072) == binding.PCMM_EUNSUPPORTED   # int32 accumulator headroom
-    assert create(K=65536, wbits=16) == binding.PCMM_EUNSUPPORTED
+    assert create(K=(1 << 22) - 127) == binding.PCMM_EINVAL   # largest K is 2^22 - 128
+    assert create(M=(1 << 24) + 1) == binding.PCMM_EINVAL
+    assert create(N=(1 << 22) + 1) == binding.PCMM_EINVAL
     big = (ctypes.c_uint64 * 1)((1 << 60) - 93)             # odd 60-bit number: 8 digits + 2 slices
     assert create(primes=ctypes.cast(big, ctypes.c_void_p), bits=60, wbits=16) == binding.PCMM_EUNSUPPORTED
     assert lib.pcmm_plan_create(None, 4, 4, 4, 1, qp, 36, 8, dummy, 0, None) == binding.PCMM_EINVAL

@@ -121,6 +121,43 @@ def test_adversarial_extremes_and_int32_headroom(gpu_device, bits, wbits, K):
     assert (got[:, 2, :] == 0).all() and (got[:, :, 1] == 0).all()
 
 
+@pytest.mark.parametrize("bits,wbits,K,launches", [(36, 8, 131072, 2), (36, 8, 130944 + 130, 2), (50, 16, 131000, 3),
+                                                   (62, 8, 131073, 2), (54, 16, 65409, 2)])
+def test_contraction_longer_than_one_launch_holds(gpu_device, bits, wbits, K, launches):
+    """K beyond the int32 headroom of one launch (130944 values of k for int8 W, 65408 for int16 W):
+    the MFMA kernel runs once per range of k and adds modulo q.  Extreme weight rows and digit
+    patterns, so that the accumulators of the full ranges reach their largest magnitude."""
+    from oracle import pcmm_oracle
+
+    per_launch = 130944 if wbits == 8 else 65408
+    assert -(-K // per_launch) == launches
+    rng = np.random.default_rng(bits * 11 + K)
+    primes = pi.ntt_primes(bits, 1 << 12, 2)
+    M, Ncols = 20, 40
+    if wbits == 8:
+        W = rng.integers(-128, 128, size=(M, K)).astype(np.int8)
+        W[0, :], W[1, :] = -128, 127
+    else:
+        W = rng.integers(-32768, 32640, size=(M, K)).astype(np.int16)
+        W[0, :], W[1, :] = -32768, 32639
+    W[2, :] = 0
+    W[3, :per_launch] = 0                                # only the later ranges contribute to row 3
+    W[4, per_launch:] = 0                                # only the first range contributes to row 4
+    A = np.stack([_digit_pattern_residues(q, bits, K, Ncols, rng) for q in primes])
+    nbytes = (bits + 7) // 8
+    for j, q in enumerate(primes):
+        A[j, :, 0] = q - 1
+        v = int.from_bytes(bytes([0x80]) * nbytes, "little") & ((1 << bits) - 1)   # digits all -128
+        while v >= q:
+            v >>= 1
+        A[j, :, 2] = v
+    A[:, :, 1] = 0
+    got, _ = _run_gpu(W, A, primes, bits, gpu_device)
+    want = pcmm_oracle(W, A, primes)
+    assert (got == want).all(), int((got != want).sum())
+    assert (got[:, 2, :] == 0).all() and (got[:, :, 1] == 0).all()
+
+
 def test_closed_forms_on_the_gpu(gpu_device):
     rng = np.random.default_rng(3)
     primes = pi.ntt_primes(36, 1 << 13, 2)
@@ -212,9 +249,9 @@ def test_int16_out_of_range_and_bad_arguments_are_status_codes(gpu_device):
         with pytest.raises(pkg.PcmmError) as e:
             pkg.pcmm_plan_create(W8, bad_primes, bits, 16)
         assert e.value.status == pkg.pcmm.PCMM_EINVAL
-    Wbig = torch.zeros((1, 131072), dtype=torch.int8, device=gpu_device)
-    with pytest.raises(pkg.PcmmError) as e:
-        pkg.pcmm_plan_create(Wbig, [primes[0]], 50, 16)
+    W16 = torch.zeros((4, 8), dtype=torch.int16, device=gpu_device)
+    with pytest.raises(pkg.PcmmError) as e:                     # 8 digits + 2 slices: 9 accumulators
+        pkg.pcmm_plan_create(W16, pi.ntt_primes(60, 1 << 12, 1), 60, 16)
     assert e.value.status == pkg.pcmm.PCMM_EUNSUPPORTED
 
 
