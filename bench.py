@@ -72,6 +72,36 @@ def cpu_baseline(wl, W_host, A_dev, C_dev, rows_target_s: float = 8.0):
     }
 
 
+def ring_switch_rates(pkg, torch, dev, iters: int = 10):
+    """The permutation kernels either side of the PCMM (not part of the timed step): HBM GB/s on a batch of
+    4 limbs x 2 components x 512 ciphertexts over R_{2^16}, decomposed to R_{2^12} (k = 16) and R_{2^8} (k = 256)."""
+    npoly, N = 4 * 2 * 512, 1 << 16
+    p = torch.randint(0, 1 << 62, (npoly, N), dtype=torch.int64, device=dev)
+    parts = torch.empty_like(p)
+    back = torch.empty_like(p)
+    stream = torch.cuda.current_stream()
+    out = {"workload": "%d polynomials of degree 2^16 (4 limbs x 2 components x 512 ciphertexts), uint64" % npoly,
+           "algorithmic_bytes_per_coefficient": 16, "hbm_peak_GBs": HBM_PEAK_GBS}
+    for k in (16, 256):
+        rates = {}
+        for name, fn, src, dst in (("decompose", pkg.pcmm_ring_decompose, p, parts),
+                                   ("compose", pkg.pcmm_ring_compose, parts, back)):
+            fn(src, dst, N, k, stream)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(iters):
+                fn(src, dst, N, k, stream)
+            e1.record(stream)
+            e1.synchronize()
+            ms = e0.elapsed_time(e1) / iters
+            rates[name + "_ms"] = ms
+            rates[name + "_GBs"] = 16.0 * npoly * N / (ms * 1e-3) / 1e9
+            rates[name + "_frac_of_hbm_peak"] = rates[name + "_GBs"] / HBM_PEAK_GBS
+        rates["round_trip_exact"] = bool(torch.equal(back, p))
+        out["k=%d" % k] = rates
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -79,6 +109,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="attn_proj")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ring-switch", action="store_true",
+                    help="skip the (untimed-step) measurement of the ring-switch permutation kernels")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -187,6 +219,10 @@ def main() -> int:
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, W_host, A_dev, C_dev)
     pkg.pcmm_plan_destroy(plan)
+    del A_dev, C_dev, W_dev
+    torch.cuda.empty_cache()
+    if not args.no_ring_switch:
+        result["ring_switch"] = ring_switch_rates(pkg, torch, dev)
     print(json.dumps(result))
     return 0
 

@@ -113,6 +113,31 @@ pcmm_status pcmm_run_profiled(const pcmm_plan *plan, const uint64_t *A_dev, uint
 pcmm_status pcmm_mfma_probe(int32_t device, int32_t iters, int32_t random_operands, double *tops_out,
                             double *shader_mhz_out);
 
+/*
+ * Ring switching, the coefficient permutation either side of the PCMM (Section 3.3, the
+ * coefficient-encoding case): after the key switch to a secret of the sub-ring R_{N'}, N' = N / k, every
+ * component p (a' or b', one RNS limb) of a ciphertext over R_N is decomposed as
+ *
+ *     p(X) = sum_{j<k} p_j(X^k) X^j ,   p_j in R_{N'} :   p_j[i] = p[i*k + j] .
+ *
+ * pcmm_ring_decompose:  in_dev [npoly][N]  ->  out_dev [npoly][k][N/k]
+ * pcmm_ring_compose:    in_dev [npoly][k][N/k]  ->  out_dev [npoly][N]      (the inverse map)
+ *
+ *   in_dev, out_dev   device, uint64 words (any content: the words are moved, not interpreted);
+ *                     must not overlap; out_dev is written completely
+ *   npoly             number of polynomials (limbs x components x ciphertexts), >= 1
+ *   N, k              powers of two, 1 <= k <= N <= 2^24 (the paper uses N = 2^16 with N' = 2^12 or 2^8)
+ *   device, stream    HIP device ordinal and hipStream_t (NULL = default stream); asynchronous
+ *
+ * No scratch memory, no plan.  The key switch that precedes the decomposition is not part of this
+ * library.  PCMM_EINVAL for null or aliased pointers and sizes that are not powers of two;
+ * PCMM_EUNSUPPORTED beyond 2^40 words or 2^31 - 1 tiles of 4096 words.
+ */
+pcmm_status pcmm_ring_decompose(const uint64_t *in_dev, uint64_t *out_dev, int64_t npoly, int64_t N, int64_t k,
+                                int32_t device, void *stream);
+pcmm_status pcmm_ring_compose(const uint64_t *in_dev, uint64_t *out_dev, int64_t npoly, int64_t N, int64_t k,
+                              int32_t device, void *stream);
+
 /* Frees everything the plan owns.  The caller makes sure no run of the plan is still in flight. */
 void pcmm_plan_destroy(pcmm_plan *plan);
 

@@ -12,6 +12,8 @@ from .pcmm import (  # noqa: F401
     pcmm_plan_destroy,
     pcmm_plan_digits,
     pcmm_plan_workspace_bytes,
+    pcmm_ring_compose,
+    pcmm_ring_decompose,
     pcmm_run,
     pcmm_run_profiled,
     pcmm_status_str,

@@ -504,6 +504,61 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
 }
 
 // ------------------------------------------------------------------------------------------------
+// ring switching: coefficient permutation either side of the PCMM (HBM-bound)
+// ------------------------------------------------------------------------------------------------
+// out[p][c][r] = in[p][r][c] for npoly matrices of R x C 64-bit words, R and C powers of two.
+// Decomposition p(X) = sum_j p_j(X^k) X^j is the case R = N/k, C = k (coefficient i*k + j of p becomes
+// coefficient i of p_j); composition is R = k, C = N/k.  One block moves a TR x TC tile (TR*TC = 4096
+// words unless the matrix is smaller) through LDS, so that both the reads (along c) and the writes
+// (along r) are contiguous runs of at least 128 bytes whenever the matrix allows it.  The row pitch
+// TC + 1 keeps the column-wise LDS reads off a single bank.
+constexpr int kTransposeWords = 4096;   // words per tile
+constexpr int kTransposeMaxTR = 512;    // most rows per tile (tiles of narrow matrices)
+__global__ __launch_bounds__(256) void transpose_u64_kernel(const uint64_t *__restrict__ in, uint64_t *__restrict__ out,
+                                                            int64_t R, int64_t C, int lTR, int lTC, int64_t tiles_r,
+                                                            int64_t tiles_c)
+{
+    __shared__ uint64_t tile[kTransposeWords + kTransposeMaxTR];     // TR * (TC + 1) words at most
+    const int TR = 1 << lTR, TC = 1 << lTC;
+    const int64_t b = blockIdx.x;
+    const int64_t tc = b % tiles_c, tr = (b / tiles_c) % tiles_r, poly = b / (tiles_c * tiles_r);
+    const uint64_t *src = in + poly * R * C + (tr << lTR) * C + (tc << lTC);
+    uint64_t *dst = out + poly * R * C + (tc << lTC) * R + (tr << lTR);
+    const int n = TR * TC;
+    const int pitch = TC + 1;
+    if (n == kTransposeWords) {   // full tile: 16 words per thread, all loads in flight before the first use
+        uint64_t v[16];
+#pragma unroll
+        for (int s = 0; s < 16; ++s) {
+            const int idx = threadIdx.x + 256 * s;
+            v[s] = src[(int64_t)(idx >> lTC) * C + (idx & (TC - 1))];
+        }
+#pragma unroll
+        for (int s = 0; s < 16; ++s) {
+            const int idx = threadIdx.x + 256 * s;
+            tile[(idx >> lTC) * pitch + (idx & (TC - 1))] = v[s];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < 16; ++s) {
+            const int idx = threadIdx.x + 256 * s;
+            const int c = idx >> lTR, r = idx & (TR - 1);
+            dst[(int64_t)c * R + r] = tile[r * pitch + c];
+        }
+        return;
+    }
+    for (int idx = threadIdx.x; idx < n; idx += 256) {
+        const int r = idx >> lTC, c = idx & (TC - 1);
+        tile[r * pitch + c] = src[(int64_t)r * C + c];
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < n; idx += 256) {
+        const int c = idx >> lTR, r = idx & (TR - 1);
+        dst[(int64_t)c * R + r] = tile[r * pitch + c];
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // measurement: register-resident MFMA-only probe
 // ------------------------------------------------------------------------------------------------
 // 40 independent accumulators per wave (the footprint of the D = 5 main loop), four W-like and ten
@@ -931,6 +986,61 @@ pcmm_status pcmm_mfma_probe(int32_t device, int32_t iters, int32_t random_operan
     if (e1) (void)hipEventDestroy(e1);
     (void)hipFree(dev);
     return rc;
+}
+
+namespace {
+
+int log2_exact(int64_t v)   // -1 unless v is a power of two
+{
+    if (v <= 0 || (v & (v - 1))) return -1;
+    int l = 0;
+    while (((int64_t)1 << l) < v) ++l;
+    return l;
+}
+
+// out[p][c][r] = in[p][r][c], R x C words, both powers of two
+pcmm_status launch_transpose(const uint64_t *in, uint64_t *out, int64_t npoly, int64_t R, int64_t C, int32_t device,
+                             hipStream_t st)
+{
+    const int lR = log2_exact(R), lC = log2_exact(C);
+    if (lR < 0 || lC < 0) return PCMM_EINVAL;
+    int lTC = std::min(lC, 6);
+    int lTR = std::min(lR, std::min(12 - lTC, 9));       // TR * TC <= 4096, TR <= 512
+    lTC = std::min(lC, 12 - lTR);                         // a short matrix gets wider tiles
+    const int64_t tiles_r = R >> lTR, tiles_c = C >> lTC;
+    const int64_t blocks = npoly * tiles_r * tiles_c;
+    if (blocks > 0x7fffffff) return PCMM_EUNSUPPORTED;
+    DevGuard dg(device);
+    if (!dg.ok) return PCMM_EDEVICE;
+    hipLaunchKernelGGL(transpose_u64_kernel, dim3((unsigned)blocks), dim3(256), 0, st, in, out, R, C, lTR, lTC, tiles_r,
+                       tiles_c);
+    return hipGetLastError() == hipSuccess ? PCMM_OK : PCMM_EDEVICE;
+}
+
+pcmm_status ring_args_ok(const void *in, const void *out, int64_t npoly, int64_t N, int64_t k, int32_t device)
+{
+    if (!in || !out || in == out || npoly <= 0 || device < 0) return PCMM_EINVAL;
+    if (log2_exact(N) < 0 || log2_exact(k) < 0 || k > N || N > ((int64_t)1 << 24)) return PCMM_EINVAL;
+    if (npoly > ((int64_t)1 << 40) / N) return PCMM_EUNSUPPORTED;
+    return PCMM_OK;
+}
+
+}  // namespace
+
+pcmm_status pcmm_ring_decompose(const uint64_t *in_dev, uint64_t *out_dev, int64_t npoly, int64_t N, int64_t k,
+                                int32_t device, void *stream)
+{
+    const pcmm_status rc = ring_args_ok(in_dev, out_dev, npoly, N, k, device);
+    if (rc != PCMM_OK) return rc;
+    return launch_transpose(in_dev, out_dev, npoly, N / k, k, device, (hipStream_t)stream);
+}
+
+pcmm_status pcmm_ring_compose(const uint64_t *in_dev, uint64_t *out_dev, int64_t npoly, int64_t N, int64_t k,
+                              int32_t device, void *stream)
+{
+    const pcmm_status rc = ring_args_ok(in_dev, out_dev, npoly, N, k, device);
+    if (rc != PCMM_OK) return rc;
+    return launch_transpose(in_dev, out_dev, npoly, k, N / k, device, (hipStream_t)stream);
 }
 
 void pcmm_plan_destroy(pcmm_plan *plan)

@@ -23,6 +23,8 @@ EXPORTED = (
     "pcmm_plan_destroy",
     "pcmm_status_str",
     "pcmm_mfma_probe",
+    "pcmm_ring_decompose",
+    "pcmm_ring_compose",
 )
 
 _lib: Optional[ctypes.CDLL] = None
@@ -55,6 +57,9 @@ def load_library() -> ctypes.CDLL:
     lib.pcmm_run_profiled.restype = ctypes.c_int
     lib.pcmm_mfma_probe.argtypes = [i32, i32, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     lib.pcmm_mfma_probe.restype = ctypes.c_int
+    for fn in (lib.pcmm_ring_decompose, lib.pcmm_ring_compose):
+        fn.argtypes = [vp, vp, i64, i64, i64, i32, vp]
+        fn.restype = ctypes.c_int
     lib.pcmm_plan_destroy.argtypes = [vp]
     lib.pcmm_plan_destroy.restype = None
     lib.pcmm_status_str.argtypes = [ctypes.c_int]
@@ -157,6 +162,29 @@ def pcmm_mfma_probe(device: int = 0, iters: int = 200000, random_operands: bool 
     if rc != PCMM_OK:
         raise PcmmError(rc, "pcmm_mfma_probe")
     return float(tops.value), float(mhz.value)
+
+
+def _ring_call(name: str, src: torch.Tensor, dst: torch.Tensor, N: int, k: int, stream) -> None:
+    for t in (src, dst):
+        if not t.is_cuda or not t.is_contiguous() or t.dtype not in (torch.int64, torch.uint64):
+            raise ValueError("ring switching moves contiguous 64-bit integer tensors on the GPU")
+    if src.device != dst.device or src.numel() != dst.numel() or src.numel() % int(N):
+        raise ValueError("source and destination must hold the same whole number of polynomials of degree N")
+    with torch.cuda.device(src.device):
+        rc = getattr(load_library(), name)(src.data_ptr(), dst.data_ptr(), src.numel() // int(N), int(N), int(k),
+                                           src.device.index, _stream_handle(stream))
+    if rc != PCMM_OK:
+        raise PcmmError(rc, name)
+
+
+def pcmm_ring_decompose(p: torch.Tensor, parts: torch.Tensor, N: int, k: int, stream=None) -> None:
+    """parts[..., j, i] = p[..., i*k + j]: p is [..][N], parts is [..][k][N/k]. Asynchronous."""
+    _ring_call("pcmm_ring_decompose", p, parts, N, k, stream)
+
+
+def pcmm_ring_compose(parts: torch.Tensor, p: torch.Tensor, N: int, k: int, stream=None) -> None:
+    """p[..., i*k + j] = parts[..., j, i]: the inverse of pcmm_ring_decompose. Asynchronous."""
+    _ring_call("pcmm_ring_compose", parts, p, N, k, stream)
 
 
 def pcmm_plan_destroy(plan: PcmmPlan) -> None:

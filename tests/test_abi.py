@@ -69,3 +69,13 @@ def test_argument_validation_needs_no_device():
     assert lib.pcmm_mfma_probe(-1, 10, 1, ctypes.byref(tops), ctypes.byref(mhz)) == binding.PCMM_EINVAL
     assert lib.pcmm_mfma_probe(0, 0, 1, ctypes.byref(tops), ctypes.byref(mhz)) == binding.PCMM_EINVAL
     assert lib.pcmm_mfma_probe(0, 10, 1, None, ctypes.byref(mhz)) == binding.PCMM_EINVAL
+    for fn in (lib.pcmm_ring_decompose, lib.pcmm_ring_compose):
+        assert fn(None, dummy, 1, 64, 8, 0, None) == binding.PCMM_EINVAL
+        assert fn(dummy, dummy, 1, 64, 8, 0, None) == binding.PCMM_EINVAL          # aliased
+        other = ctypes.c_void_p(0x2000)
+        assert fn(dummy, other, 0, 64, 8, 0, None) == binding.PCMM_EINVAL
+        assert fn(dummy, other, 1, 96, 8, 0, None) == binding.PCMM_EINVAL          # N not a power of two
+        assert fn(dummy, other, 1, 64, 3, 0, None) == binding.PCMM_EINVAL
+        assert fn(dummy, other, 1, 64, 128, 0, None) == binding.PCMM_EINVAL        # k > N
+        assert fn(dummy, other, 1, 64, 8, -1, None) == binding.PCMM_EINVAL
+        assert fn(dummy, other, 1 << 36, 1 << 16, 8, 0, None) == binding.PCMM_EUNSUPPORTED
