@@ -2,12 +2,15 @@
 // components (the clear matrix product that the paper's linear-layer PCMM reduces to, Sections 2.2,
 // 3.2 and 5.1; ciphertexts as pairs in R_Q^2 with component-wise addition, Appendix A).
 //
-// Three kernels:
+// Kernels of the PCMM path:
 //   pack_w_kernel   (plan time)  W -> int8 slices in MFMA A-operand fragment order
 //   split_kernel    (every run)  uint64 residues -> D signed base-256 digit planes in MFMA
 //                                B-operand fragment order
 //   gemm_kernel     (every run)  v_mfma_i32_16x16x64_i8 main loop, then recombination of the digit
-//                                accumulators and Barrett reduction modulo q_j
+//                                accumulators and reduction modulo q_j
+// Beside it:
+//   transpose_u64_kernel         the coefficient permutation of ring switching (Section 3.3)
+//   mfma_probe_kernel            measurement aid: what the matrix cores sustain without memory traffic
 //
 // Fragment order.  One v_mfma_i32_16x16x64_i8 operand is 16 (rows or columns) x 64 (k) int8: lane l
 // of the wave holds the 16 bytes with index (l % 16) and k = 16*(l/16) .. 16*(l/16)+15.  Both
@@ -25,7 +28,6 @@
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
-typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 
 constexpr int kFrag = 1024;   // bytes of one 16 x 64 int8 MFMA operand fragment
