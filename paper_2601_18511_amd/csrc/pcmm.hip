@@ -48,7 +48,9 @@ struct LimbConst {
 enum Epi : int {
     EPI_F64 = 0,     // q < 2^50: exact double-precision arithmetic (fma remainders), no 64-bit multiplies
     EPI_INT1 = 1,    // any q < 2^62, value known to fit 62 bits: one 64-bit Barrett
-    EPI_INT2 = 2     // any q < 2^62: two Barretts and one Shoup multiplication by 2^32
+    EPI_INT2 = 2,    // any q < 2^62: two Barretts and one Shoup multiplication by 2^32
+    EPI_F64_G4 = 3,  // as EPI_F64 with the accumulators grouped in fours: |acc| < 2^28, 7 or 8 accumulators
+    EPI_F64_G4P = 4  // as EPI_F64_G4 with pairs of accumulators first joined in int32: 257 |acc| < 2^31
 };
 
 // ------------------------------------------------------------------------------------------------
@@ -126,43 +128,87 @@ __device__ __forceinline__ void mfma_drain()
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 }
 
-// Exact reduction in double precision.  `t` holds E integers of magnitude < 2^31 (as doubles);
-// returns (sum_e t[e] 256^e) mod q in [0, q) for 2^23 < q < 2^50.
+// Exact reduction in double precision.  `a` holds E int32 accumulators; returns (sum_e a[e] 256^e) mod q
+// in [0, q) for 2^23 < q < 2^50.
 //
-// The accumulators are grouped in threes from the bottom, c_g = t[3g] + 2^8 t[3g+1] + 2^16 t[3g+2]
-// (|c_g| < 2^47.01, exact).  Horner in base 2^24 from the top group, one step per group:
-//   X  = r 2^24                      exact (power-of-two scaling)
+// The accumulators are grouped from the bottom into G-digit numbers, G = 3 in general:
+// c_g = a[3g] + 2^8 a[3g+1] + 2^16 a[3g+2] (|c_g| < 2^47.01, exact in a double).  Horner in base
+// B = 2^(8G) from the top group, one step per group:
+//   X  = r B                         exact (power-of-two scaling)
 //   qh = rint((X + c_g) / q)         the sum and the quotient are rounded: qh = (X + c_g)/q + eta with
 //                                    |eta| <= 0.5 + 3.01 * 2^-53 * |X + c_g|/q  <=  0.6
-//                                    (|X + c_g|/q < 2^48.01 in the first step, where r = c_top is not yet
-//                                    reduced, and < 2^24 afterwards)
-//   u  = fma(-qh, q, X)              = -c_g - eta q exactly: an integer of magnitude below 2^52
+//                                    (G = 3: |X + c_g|/q < 2^48.01 in the first step, where r = c_top is not
+//                                    yet reduced, and < 2^24 afterwards)
+//   u  = fma(-qh, q, X)              = -c_g - eta q exactly: an integer of magnitude below 2^53
 //   r  = u + c_g                     = -eta q exactly, so |r| <= 0.6 q
 // After the last group a negative r is lifted by q, which lands in [0, q) because |r| <= 0.6 q.
 // Every operation is exact or feeds the rint whose error the exact fma absorbs, so the result is the
 // canonical residue bit for bit.
-template <int E>
-__device__ __forceinline__ uint64_t reduce_f64(const double (&t)[E], double q, double invq)
+//
+// MODE 1 (E = 7 or 8 accumulators of magnitude < 2^28, q > 2^37): G = 4, so that two groups and a single
+// Horner step remain.  |c_g| < 2^28 (1 + 2^8 + 2^16 + 2^24) < 2^52.01 is still exact, |X + c_g| < 2^84.02
+// in the one step gives |X + c_g|/q < 2^47.1 and |eta| <= 0.5 + 3.01 * 2^-5.9 < 0.56, and
+// |u| <= |c_g| + 0.56 q < 2^53.
+// MODE 2 (in addition 257 |acc| < 2^31): neighbouring accumulators are first joined in int32,
+// p = a[2i] + 2^8 a[2i+1], which halves the conversions to double.
+// R outputs are reduced side by side, stage by stage: R independent dependency chains in the order the
+// scheduler should issue them.
+template <int E, int MODE, int R>
+__device__ __forceinline__ void reduce_f64(const int (&a)[R][E], double q, double invq, uint64_t (&res)[R])
 {
-    constexpr int G = (E + 2) / 3;
+    constexpr int GS = MODE == 0 ? 3 : 4;            // accumulators per group
+    constexpr int G = (E + GS - 1) / GS;
     static_assert(G >= 2, "at least one Horner step");
-    double c[G];
+    static_assert(MODE == 0 || G == 2, "groups of four are proved for a single Horner step");
+    double c[G][R];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        c[g] = t[3 * g];
-        if (3 * g + 1 < E) c[g] = __builtin_fma(t[3 * g + 1], 256.0, c[g]);
-        if (3 * g + 2 < E) c[g] = __builtin_fma(t[3 * g + 2], 65536.0, c[g]);
+        const int b0 = GS * g;
+        if constexpr (MODE == 2) {
+            int p0[R], p1[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                p0[r] = b0 + 1 < E ? a[r][b0] + (int)((unsigned)a[r][b0 + 1] << 8) : a[r][b0];
+                if (b0 + 2 < E) p1[r] = b0 + 3 < E ? a[r][b0 + 2] + (int)((unsigned)a[r][b0 + 3] << 8) : a[r][b0 + 2];
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r) c[g][r] = (double)p0[r];
+            if (b0 + 2 < E) {
+#pragma unroll
+                for (int r = 0; r < R; ++r) c[g][r] = __builtin_fma((double)p1[r], 65536.0, c[g][r]);
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < R; ++r) c[g][r] = (double)a[r][b0];
+#pragma unroll
+            for (int i = 1; i < GS; ++i)
+                if (b0 + i < E) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+                        c[g][r] = __builtin_fma((double)a[r][b0 + i], (double)(1 << (8 * i)), c[g][r]);
+                }
+        }
     }
-    double r = c[G - 1];
+    constexpr double B = MODE == 0 ? 16777216.0 : 4294967296.0;
+    double rr[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) rr[r] = c[G - 1][r];
 #pragma unroll
     for (int g = G - 2; g >= 0; --g) {
-        const double X = r * 16777216.0;
-        const double qh = __builtin_rint((X + c[g]) * invq);
-        r = __builtin_fma(-qh, q, X) + c[g];
+        double X[R], qh[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) X[r] = rr[r] * B;
+#pragma unroll
+        for (int r = 0; r < R; ++r) qh[r] = __builtin_rint((X[r] + c[g][r]) * invq);
+#pragma unroll
+        for (int r = 0; r < R; ++r) rr[r] = __builtin_fma(-qh[r], q, X[r]) + c[g][r];
     }
-    r = r < 0.0 ? r + q : r;
-    // r is an integer in [0, 2^52): adding 2^52 places it in the low mantissa bits
-    return (uint64_t)__double_as_longlong(r + 4503599627370496.0) & 0x000FFFFFFFFFFFFFull;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const double v = rr[r] < 0.0 ? rr[r] + q : rr[r];
+        // v is an integer in [0, 2^52): adding 2^52 places it in the low mantissa bits
+        res[r] = (uint64_t)__double_as_longlong(v + 4503599627370496.0) & 0x000FFFFFFFFFFFFFull;
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -320,7 +366,6 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
     // scalar registers and loads take the (scalar base + 32-bit lane offset) form
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nkb = a.nkbc;                                   // k-steps of this launch, numbered from 0 below
-    const int last = nkb - 1;
     const int64_t kleft = a.nkb - a.kb0;                      // k-steps from kb0 to the end of the layouts
 
     // chunk kb0 of this tile; k-step stride ntiles*CH
@@ -377,27 +422,49 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
     constexpr int CNT = D * S * MT;                  // MFMAs per half k-step
     constexpr int NW = S * MT;                       // W fragments per k-step
 
-    // prologue
+    // prologue: everything the first k-step and the LDS fill of the second need is requested at once,
+    // so that a tile start pays one memory latency, not two (nkb >= 2).  The limb's constants come
+    // first and are moved to scalar registers: a vector load still in flight when the epilogue
+    // branches around padding blocks would make the compiler wait for it behind the first stores.
+    LimbConst lc;
+    {
+        constexpr int LCW = sizeof(LimbConst) / 4;
+        static_assert(sizeof(LimbConst) % 4 == 0, "LimbConst is read word by word");
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(a.lc + limb);
+        uint32_t w[LCW];
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) areg[i] = ld_a(uoff[i], 0);
+        for (int i = 0; i < LCW; ++i) w[i] = src[i];
+        v4i first[NLD];
 #pragma unroll
-    for (int f = 0; f < NW; ++f) wreg[0][f / MT][f % MT] = ld_w(f / MT, f % MT, 0);
+        for (int i = 0; i < NLD; ++i) first[i] = ld_a(uoff[i], 0);
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) *reinterpret_cast<v4i *>(&lds[0][uoff[i]]) = areg[i];
+        for (int f = 0; f < NW; ++f) wreg[0][f / MT][f % MT] = ld_w(f / MT, f % MT, 0);
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) areg[i] = ld_a(uoff[i], min(1, last));
+        for (int i = 0; i < NLD; ++i) areg[i] = ld_a(uoff[i], 1);
+#pragma unroll
+        for (int i = 0; i < LCW; ++i) w[i] = __builtin_amdgcn_readfirstlane(w[i]);
+        __builtin_memcpy(&lc, w, sizeof(lc));
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) *reinterpret_cast<v4i *>(&lds[0][uoff[i]]) = first[i];
+    }
     __syncthreads();
 
-    auto step = [&](auto phase, int kb) {
+    // One k-step.  FILL: k-step kb+1 exists (fetch its W fragments, move its digit chunk to LDS);
+    // AHEAD: k-step kb+2 exists (request its digit chunk).  The last two k-steps run without the
+    // loads that would have nowhere to go, so that no load is in flight when the epilogue starts: a
+    // wait for one placed behind the first stores would, the counter being in order, wait for those
+    // stores to complete.
+    auto step = [&](auto phase, auto fill, auto ahead, int kb) {
         constexpr int CUR = decltype(phase)::value, NXT = CUR ^ 1;
-        const int kw = min(kb + 1, last);
-        const int ka = min(kb + 2, last);
+        constexpr bool FILL = decltype(fill)::value, AHEAD = decltype(ahead)::value;
+        const int kw = kb + 1;
+        const int ka = kb + 2;
 #pragma unroll
         for (int d = 0; d < D; ++d) b[d] = *reinterpret_cast<const v4i *>(&lds[CUR][d * kFrag + lane * 16]);
         // first half: W loads of k-step kb+1 and LDS writes of chunk kb+1 between the MFMAs
         static_for<CNT>([&](auto mc) {
             constexpr int m = decltype(mc)::value;
-            constexpr int OPS = NW + NLD;
+            constexpr int OPS = FILL ? NW + NLD : 0;
             constexpr int n_lo = (m * OPS + CNT - 1) / CNT, n_hi = ((m + 1) * OPS + CNT - 1) / CNT;
             static_for<n_hi - n_lo>([&](auto jc) {
                 constexpr int n = n_lo + decltype(jc)::value;
@@ -415,7 +482,7 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
         // second half: loads of digit chunk kb+2 between the MFMAs
         static_for<CNT>([&](auto mc) {
             constexpr int m = decltype(mc)::value;
-            constexpr int OPS = NLD;
+            constexpr int OPS = AHEAD ? NLD : 0;
             constexpr int n_lo = (m * OPS + CNT - 1) / CNT, n_hi = ((m + 1) * OPS + CNT - 1) / CNT;
             static_for<n_hi - n_lo>([&](auto jc) {
                 constexpr int n = n_lo + decltype(jc)::value;
@@ -424,15 +491,25 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
             constexpr int d = m / NW, ws = (m / MT) % S, wi = m % MT;
             mfma_i8<4 * ((wi * NT + 1) * E + d + ws)>(wreg[CUR][ws][wi], b[d]);
         });
-        __syncthreads();
+        if constexpr (FILL) __syncthreads();   // chunk kb+1 is in LDS; buffer CUR may be refilled
     };
-    for (int kb = 0; kb < nkb; kb += 2) {   // nkb is even
-        step(std::integral_constant<int, 0>{}, kb);
-        step(std::integral_constant<int, 1>{}, kb + 1);
+    {
+        using P0 = std::integral_constant<int, 0>;
+        using P1 = std::integral_constant<int, 1>;
+        int kb = 0;
+        for (; kb < nkb - 2; kb += 2) {   // nkb is even
+            step(P0{}, std::true_type{}, std::true_type{}, kb);
+            step(P1{}, std::true_type{}, std::true_type{}, kb + 1);
+        }
+        step(P0{}, std::true_type{}, std::false_type{}, kb);
+        step(P1{}, std::false_type{}, std::false_type{}, kb + 1);
     }
 
     // volatile asm statements keep their order: last MFMA, drain, accumulator reads
     mfma_drain();
+    // Every load has been consumed by now.  Saying so with a wait the compiler sees keeps it from
+    // placing one of its own (for a load it cannot prove finished on some path) behind the first stores.
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
 
     // ---- epilogue.  Accumulator register r of lane l is output row 4*(l/16)+r, column l%16 of its
     // 16 x 16 block.
@@ -440,7 +517,6 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
     // rows at or beyond M fall outside it and are dropped by the range check, and lanes whose column
     // is at or beyond Ncols get an offset that is out of range for every row; no address arithmetic
     // or branching per output.
-    const LimbConst lc = a.lc[limb];
     uint64_t *Cl = a.C + (int64_t)limb * a.M * a.Ncols;
     const uint32_t c_rowbytes = (uint32_t)a.Ncols * 8u;
     // The whole epilogue exists twice, with and without the read-add of the previous contents of C,
@@ -458,46 +534,57 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
             const int64_t n = ((int64_t)tn * NT + j) * 16 + (lane & 15);
             const uint32_t c_lane = n < a.Ncols ? (uint32_t)((lane >> 4) * 4) * c_rowbytes + (uint32_t)n * 8u
                                                 : 0x80000000u;
-            static_for<4>([&](auto rc) {
-                constexpr int r = decltype(rc)::value;
-                int av[E];
-                static_for<E>([&](auto ec) {
-                    constexpr int e = decltype(ec)::value;
-                    av[e] = acc_read<4 * ((i * NT + j) * E + e) + r>();
-                });
-                uint64_t res;
-                if constexpr (EPI == EPI_F64) {
-                    double t[E];
+            // all accumulators of the block's four outputs first (the reads are volatile and keep their
+            // order), so that the four reductions are independent chains the scheduler can interleave
+            int avs[4][E];
+            static_for<4 * E>([&](auto rec) {
+                constexpr int r = decltype(rec)::value / E, e = decltype(rec)::value % E;
+                avs[r][e] = acc_read<4 * ((i * NT + j) * E + e) + r>();
+            });
+            uint64_t res[4];
+            if constexpr (EPI == EPI_F64) {
+                reduce_f64<E, 0, 4>(avs, lc.qd, lc.invq, res);
+            } else if constexpr (EPI == EPI_F64_G4) {
+                reduce_f64<E, 1, 4>(avs, lc.qd, lc.invq, res);
+            } else if constexpr (EPI == EPI_F64_G4P) {
+                reduce_f64<E, 2, 4>(avs, lc.qd, lc.invq, res);
+            } else {
 #pragma unroll
-                    for (int e = 0; e < E; ++e) t[e] = (double)av[e];
-                    res = reduce_f64<E>(t, lc.qd, lc.invq);
-                } else {
+                for (int r = 0; r < 4; ++r) {
                     // value = vlo + 2^32 vhi with vlo, vhi of magnitude < 2^56
                     int64_t vlo = 0, vhi = 0;
 #pragma unroll
                     for (int e = 0; e < E; ++e) {
-                        int64_t v = (int64_t)av[e];
+                        int64_t v = (int64_t)avs[r][e];
                         if (e < 4) vlo += v << (8 * e);
                         else vhi += v << (8 * (e - 4));
                     }
                     if constexpr (EPI == EPI_INT1) {
                         // plan guarantees |vlo + 2^32 vhi| < 2^62
-                        res = barrett_u64((uint64_t)(vlo + (vhi << 32)) + lc.off, lc.q, lc.mu);
+                        res[r] = barrett_u64((uint64_t)(vlo + (vhi << 32)) + lc.off, lc.q, lc.mu);
                     } else {
                         uint64_t rlo = barrett_u64((uint64_t)vlo + lc.off, lc.q, lc.mu);
                         uint64_t rhi = barrett_u64((uint64_t)vhi + lc.off, lc.q, lc.mu);
-                        res = rlo + mulmod_shoup(rhi, lc.c32, lc.c32s, lc.q);
-                        if (res >= lc.q) res -= lc.q;
+                        res[r] = rlo + mulmod_shoup(rhi, lc.c32, lc.c32s, lc.q);
+                        if (res[r] >= lc.q) res[r] -= lc.q;
                     }
                 }
-                if constexpr (ACCUMULATE) {   // rows and columns outside C read as 0
-                    const v2u old = __builtin_amdgcn_raw_buffer_load_b64(crs, c_lane + (uint32_t)r * c_rowbytes, 0, 0);
-                    res += (uint64_t)old[0] | ((uint64_t)old[1] << 32);
-                    if (res >= lc.q) res -= lc.q;
+            }
+            if constexpr (ACCUMULATE) {   // rows and columns outside C read as 0
+                v2u old[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    old[r] = __builtin_amdgcn_raw_buffer_load_b64(crs, c_lane + (uint32_t)r * c_rowbytes, 0, 0);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    res[r] += (uint64_t)old[r][0] | ((uint64_t)old[r][1] << 32);
+                    if (res[r] >= lc.q) res[r] -= lc.q;
                 }
-                __builtin_amdgcn_raw_buffer_store_b64((v2u){(uint32_t)res, (uint32_t)(res >> 32)}, crs,
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                __builtin_amdgcn_raw_buffer_store_b64((v2u){(uint32_t)res[r], (uint32_t)(res[r] >> 32)}, crs,
                                                       c_lane + (uint32_t)r * c_rowbytes, 0, 0);
-            });
         }
     });
     };
@@ -657,6 +744,11 @@ hipError_t launch_gemm_ds(const pcmm_plan *p, const GemmArgs &ga, int64_t grid, 
     if (p->epi == EPI_F64) {
         if constexpr (D <= 7) hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, EPI_F64>), g, b, 0, st, ga);
         else return hipErrorInvalidValue;
+    } else if (p->epi == EPI_F64_G4 || p->epi == EPI_F64_G4P) {
+        if constexpr (D <= 7 && D + S - 1 >= 7) {
+            if (p->epi == EPI_F64_G4) hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, EPI_F64_G4>), g, b, 0, st, ga);
+            else hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, EPI_F64_G4P>), g, b, 0, st, ga);
+        } else return hipErrorInvalidValue;
     } else {
         if constexpr (D >= 7) {
             if (p->epi == EPI_INT1) hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, EPI_INT1>), g, b, 0, st, ga);
@@ -859,6 +951,13 @@ pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncol
             bound += be << (8 * e);
         }
         p->epi = qmax < ((uint64_t)1 << 50) ? EPI_F64 : (bound < ((u128)1 << 62) ? EPI_INT1 : EPI_INT2);
+        // short contractions leave small accumulators: |acc| <= S * K_launch * 2^14
+        uint64_t qmin = primes_host[0];
+        for (int j = 1; j < L; ++j) qmin = std::min(qmin, (uint64_t)primes_host[j]);
+        if (p->epi == EPI_F64 && E >= 7 && qmin > ((uint64_t)1 << 37)) {
+            if ((int64_t)S * K_launch <= 509) p->epi = EPI_F64_G4P;   // 257 * S*K * 2^14 < 2^31
+            else if ((int64_t)S * K_launch <= 16383) p->epi = EPI_F64_G4;
+        }
     }
 
     DevGuard dg(device);

@@ -96,7 +96,11 @@ def _digit_pattern_residues(q, bits, K, Ncols, rng):
 
 
 @pytest.mark.parametrize("bits,wbits,K", [(36, 8, 14336), (50, 16, 1024), (62, 8, 2048), (36, 8, 131071),
-                                          (50, 16, 65535), (24, 16, 65535)])
+                                          (50, 16, 65535), (24, 16, 65535),
+                                          # the short-contraction epilogues and the sizes where they switch
+                                          (50, 16, 254), (50, 16, 255), (50, 8, 509), (50, 8, 510),
+                                          (50, 16, 8191), (50, 16, 8192), (50, 8, 16383), (50, 8, 16384),
+                                          (40, 16, 200), (44, 16, 3000), (38, 16, 100)])
 def test_adversarial_extremes_and_int32_headroom(gpu_device, bits, wbits, K):
     """All-(-128) / all-127 weight rows against extreme digit patterns: the int32 accumulators reach
     K * 2^14 (2^27.8 at K = 14336, 2^31 - 2^14 at the largest supported K)."""
