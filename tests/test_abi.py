@@ -4,10 +4,13 @@ import ctypes
 import os
 import re
 
+import pytest
+
 import paper_2601_18511_amd as pkg
 from paper_2601_18511_amd import pcmm as binding
 
-HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "pcmm.h")
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "pcmm.h")
 
 
 def _declared_functions():
@@ -79,3 +82,34 @@ def test_argument_validation_needs_no_device():
         assert fn(dummy, other, 1, 64, 128, 0, None) == binding.PCMM_EINVAL        # k > N
         assert fn(dummy, other, 1, 64, 8, -1, None) == binding.PCMM_EINVAL
         assert fn(dummy, other, 1 << 36, 1 << 16, 8, 0, None) == binding.PCMM_EUNSUPPORTED
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/pcmm.h compiles as C99 and as C++ and declares what the binding expects."""
+    import shutil
+    import subprocess
+
+    src = tmp_path / "use_pcmm.c"
+    src.write_text(
+        '#include "pcmm.h"\n'
+        "int main(void) {\n"
+        "    pcmm_plan *p = 0;\n"
+        "    pcmm_status s = pcmm_plan_create(&p, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0);\n"
+        "    (void)pcmm_ring_decompose(0, 0, 0, 0, 0, 0, 0);\n"
+        "    pcmm_plan_destroy(p);\n"
+        "    return s == PCMM_EINVAL ? 0 : 1;\n"
+        "}\n"
+    )
+    inc = os.path.join(ROOT, "include")
+    for cc, std in (("gcc", "-std=c99"), ("g++", "-std=c++11")):
+        if shutil.which(cc) is None:
+            pytest.skip("no %s" % cc)
+        args = [cc, std, "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-I", inc]
+        if cc == "g++":
+            args += ["-x", "c++"]
+        subprocess.run(args + [str(src)], check=True)
+    # and a C program linked against the built library runs the argument checks without a device
+    exe = tmp_path / "use_pcmm"
+    subprocess.run(["gcc", "-std=c99", "-I", inc, str(src), "-o", str(exe), "-L", os.path.dirname(pkg.build.LIB),
+                    "-l:libpcmm.so", "-Wl,-rpath," + os.path.dirname(pkg.build.LIB)], check=True)
+    assert subprocess.run([str(exe)]).returncode == 0
