@@ -932,6 +932,10 @@ pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncol
     p->MB = p->mtiles * BM / 16;
     p->nkb = (K + 127) / 128 * 2;   // the main loop takes two k-steps of 64 per round
     p->nkb_launch = nkb_launch;
+    if ((int64_t)L * p->mtiles * p->ntiles > 0x7fffff00LL) {   // one work-group per tile: the grid is a 32-bit count
+        delete p;
+        return PCMM_EUNSUPPORTED;
+    }
 
     // can value = sum_e acc_e 256^e be reduced in one go?  |acc_e| <= K * sum_{s+d=e} 128 * dmax_d,
     // dmax_d = 128 except for the top digit, which is at most top = ((qmax-1+Bias) >> 8(D-1)) - 128.
