@@ -415,7 +415,7 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
     // the second wave on each SIMD issues MFMAs while the first waits on LDS, memory or the barrier.
     // Memory instructions are spread between the MFMAs, because a wave issues in order and a burst
     // of LDS writes (about 64 B/clk per CU) would hold back the MFMAs queued behind it.
-    // Loads past the last k-step are clamped to it (their data is never used).
+    // The last two k-steps run without the loads that would reach past the contraction.
     v4i wreg[2][S][MT];
     v4i areg[NLD];
     v4i b[D];
