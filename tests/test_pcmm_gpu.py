@@ -308,3 +308,33 @@ def test_pcmm_run_inside_a_hip_graph_replays_correctly(gpu_device):
         got = C_dev.cpu().numpy().view(np.uint64)
         assert (got == pcmm_oracle(W, A, primes)).all(), rep
     pkg.pcmm_plan_destroy(plan)
+
+
+def test_seeded_sweep_of_small_shapes(gpu_device):
+    """Sixty seeded shapes over every digit count, both weight widths and every epilogue variant, ragged in all
+    three dimensions, several with a single row, column or k."""
+    from oracle import pcmm_oracle
+
+    rnd = random.Random(20260118)
+    cases = []
+    for bits in (24, 28, 31, 33, 36, 40, 41, 47, 48, 49, 50, 51, 55, 56, 57, 62):
+        for wbits in (8, 16):
+            digits = next(d for d in range(1, 9) if (1 << bits) - 2 + sum(0x80 << (8 * i) for i in range(d)) < 1 << (8 * d))
+            if max(digits, 4) + wbits // 8 - 1 > 8:
+                continue                                          # more accumulators than the kernels hold
+            M = rnd.choice((1, 7, 16, 33, 64, 100, 129, 257))
+            K = rnd.choice((1, 5, 63, 64, 65, 127, 128, 129, 255, 300, 513, 700))
+            Ncols = rnd.choice((1, 2, 15, 16, 17, 31, 32, 33, 63, 100, 257))
+            cases.append((M, K, Ncols, bits, rnd.choice((1, 2, 3)), wbits))
+    rnd.shuffle(cases)
+    assert len(cases) >= 28
+    extra = [(rnd.choice((5, 80, 300)), rnd.choice((1100, 2500, 9000, 17000)), rnd.choice((3, 40, 70)), b, 1, w)
+             for b, w in ((36, 8), (50, 16), (50, 8), (44, 16), (62, 8), (54, 16))]   # longer contractions
+    for M, K, Ncols, bits, L, wbits in cases + extra:
+        rng = np.random.default_rng(M * 7919 + K * 31 + Ncols)
+        primes = pi.ntt_primes(bits, 1 << 8, L)
+        W = _rand_W(rng, M, K, wbits)
+        A = _rand_A(rng, K, Ncols, primes)
+        got, _ = _run_gpu(W, A, primes, bits, gpu_device)
+        want = pcmm_oracle(W, A, primes)
+        assert (got == want).all(), (M, K, Ncols, bits, L, wbits, int((got != want).sum()))
