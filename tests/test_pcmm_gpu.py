@@ -338,3 +338,32 @@ def test_seeded_sweep_of_small_shapes(gpu_device):
         got, _ = _run_gpu(W, A, primes, bits, gpu_device)
         want = pcmm_oracle(W, A, primes)
         assert (got == want).all(), (M, K, Ncols, bits, L, wbits, int((got != want).sum()))
+
+
+def test_two_plans_on_two_streams_at_once(gpu_device):
+    """Runs of different plans may overlap in time (each plan has its own digit scratch): two plans enqueued
+    alternately on two streams of the default priority, three rounds, every result exact."""
+    import torch
+
+    import paper_2601_18511_amd as pkg
+    from oracle import pcmm_oracle
+
+    rng = np.random.default_rng(21)
+    primes = pi.ntt_primes(36, 1 << 13, 3)
+    shapes = ((320, 1024, 2048), (192, 768, 4096))
+    Ws = [_rand_W(rng, M, K, 8) for M, K, _ in shapes]
+    As = [[_rand_A(rng, K, N, primes) for _ in range(3)] for _, K, N in shapes]
+    streams = [torch.cuda.Stream(device=gpu_device), torch.cuda.Stream(device=gpu_device)]
+    plans = [pkg.pcmm_plan_create(torch.from_numpy(W).to(gpu_device), primes, 36, N) for W, (_, _, N) in zip(Ws, shapes)]
+    A_dev = [[torch.from_numpy(a.view(np.int64)).to(gpu_device) for a in group] for group in As]
+    C_dev = [[torch.empty((3, M, N), dtype=torch.int64, device=gpu_device) for _ in range(3)] for M, _, N in shapes]
+    torch.cuda.synchronize()
+    for r in range(3):
+        for p in range(2):
+            pkg.pcmm_run(plans[p], A_dev[p][r], C_dev[p][r], streams[p])
+    torch.cuda.synchronize()
+    for p in range(2):
+        for r in range(3):
+            want = pcmm_oracle(Ws[p], As[p][r], primes)
+            assert (C_dev[p][r].cpu().numpy().view(np.uint64) == want).all(), (p, r)
+        pkg.pcmm_plan_destroy(plans[p])
