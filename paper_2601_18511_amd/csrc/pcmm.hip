@@ -346,9 +346,9 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
     __shared__ __attribute__((aligned(16))) int8_t lds[2][CH];
 
     // ---- which tile: XCD-aware raster.  Work-groups are dealt round-robin to the 8 XCDs, so
-    // bid % 8 names the XCD; each XCD walks its own contiguous range of tiles, m fastest inside
-    // groups of gn n-tiles, so that the tiles resident on one XCD share W rows and digit columns
-    // in that XCD's L2.
+    // bid % 8 names the XCD; each XCD walks its own contiguous range of tiles in groups of gn n-tiles
+    // x all m-tiles, n fastest inside a group, so that the tiles resident on one XCD (an 8 x 8 block
+    // for gn = 8) share W rows and digit columns in that XCD's L2.
     const int64_t bid = blockIdx.x;
     const int64_t t = (bid % kXcd) * a.per_xcd + bid / kXcd;
     if (bid / kXcd >= a.per_xcd || t >= a.total) return;
