@@ -102,6 +102,30 @@ def ring_switch_rates(pkg, torch, dev, iters: int = 10):
     return out
 
 
+def library_int8_gemm(torch, dev, wl, iters: int = 5):
+    """Context only: the vendor library's plain int8 GEMM (torch._int_mm) on the raw int8 products of the same
+    workload, W[M][K] x digit planes [K][Ncols*L*D] -> int32, random int8 data.  No digit split, no recombination,
+    no reduction: what 'hand the clear product to a GPU BLAS' costs on this machine for the inner products alone."""
+    try:
+        n_eq = wl.Ncols * wl.L * wl.digits
+        a = torch.randint(-128, 128, (wl.M, wl.K), dtype=torch.int8, device=dev)
+        b = torch.randint(-128, 128, (wl.K, n_eq), dtype=torch.int8, device=dev)
+        c = torch._int_mm(a, b)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            c = torch._int_mm(a, b)
+        e1.record()
+        e1.synchronize()
+        ms = e0.elapsed_time(e1) / iters
+        del a, b, c
+        tops = 2.0 * wl.M * wl.K * n_eq / (ms * 1e-3) / 1e12
+        return {"what": "torch._int_mm %dx%dx%d int8 -> int32 (inner products only)" % (wl.M, wl.K, n_eq),
+                "ms": ms * wl.slices, "tops": tops}
+    except Exception as exc:  # the library may not cover a shape; this block is context, not the product
+        return {"what": "torch._int_mm unavailable for this shape", "error": str(exc)[:200]}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -111,6 +135,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ring-switch", action="store_true",
                     help="skip the (untimed-step) measurement of the ring-switch permutation kernels")
+    ap.add_argument("--no-library-gemm", action="store_true",
+                    help="skip timing the vendor library's plain int8 GEMM on the same int8 work (context only)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -223,6 +249,8 @@ def main() -> int:
     torch.cuda.empty_cache()
     if not args.no_ring_switch:
         result["ring_switch"] = ring_switch_rates(pkg, torch, dev)
+    if not args.no_library_gemm:
+        result["library_int8_gemm"] = library_int8_gemm(torch, dev, wl)
     print(json.dumps(result))
     return 0
 
