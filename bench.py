@@ -36,7 +36,7 @@ def _traffic_from_profiles(workload: str):
     return None
 
 
-def cpu_baseline(wl, W_host, A_dev, C_dev, rows_target_s: float = 8.0):
+def cpu_baseline(wl, W_host, A_dev, C_dev, rows_target_s: float = 20.0):
     """Time the oracle (as it stands) on a bounded sample of the same workload; also checks the GPU rows."""
     import numpy as np
 
