@@ -560,7 +560,7 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
                         else vhi += v << (8 * (e - 4));
                     }
                     if constexpr (EPI == EPI_INT1) {
-                        // plan guarantees |vlo + 2^32 vhi| < 2^62
+                        // plan guarantees |vlo + 2^32 vhi| <= 2^62 - q, so that adding off makes it non-negative
                         res[r] = barrett_u64((uint64_t)(vlo + (vhi << 32)) + lc.off, lc.q, lc.mu);
                     } else {
                         uint64_t rlo = barrett_u64((uint64_t)vlo + lc.off, lc.q, lc.mu);
@@ -954,7 +954,8 @@ pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncol
             }
             bound += be << (8 * e);
         }
-        p->epi = qmax < ((uint64_t)1 << 50) ? EPI_F64 : (bound < ((u128)1 << 62) ? EPI_INT1 : EPI_INT2);
+        // one Barrett needs value + off >= 0 with off = q floor(2^62 / q) > 2^62 - q
+        p->epi = qmax < ((uint64_t)1 << 50) ? EPI_F64 : (bound + qmax <= ((u128)1 << 62) ? EPI_INT1 : EPI_INT2);
         // short contractions leave small accumulators: |acc| <= S * K_launch * 2^14
         uint64_t qmin = primes_host[0];
         for (int j = 1; j < L; ++j) qmin = std::min(qmin, (uint64_t)primes_host[j]);

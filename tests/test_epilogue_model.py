@@ -126,3 +126,66 @@ def test_values_that_are_multiples_of_q_or_one_off():
                     continue
                 assert sum(a << (8 * e) for e, a in enumerate(acc)) == target
                 assert reduce_model(acc, q, mode) == target % q
+
+
+# ---- the integer epilogues (primes of 2^50 and more): 64-bit Barrett, one piece or two pieces + Shoup
+M64 = (1 << 64) - 1
+
+
+def barrett_u64(u, q, mu):
+    assert 0 <= u <= M64
+    qhat = (u * mu) >> 64
+    r = (u - qhat * q) & M64
+    return r - q if r >= q else r
+
+
+def mulmod_shoup(x, c, cs, q):
+    qhat = (x * cs) >> 64
+    r = (x * c - qhat * q) & M64
+    return r - q if r >= q else r
+
+
+def reduce_int_model(acc, q, two_part):
+    mu = (1 << 64) // q
+    off = q * ((1 << 62) // q)
+    vlo = sum(a << (8 * e) for e, a in enumerate(acc[:4]))
+    vhi = sum(a << (8 * (e - 4)) for e, a in enumerate(acc) if e >= 4)
+    if not two_part:
+        v = vlo + (vhi << 32)
+        assert abs(v) <= (1 << 62) - q                         # what the plan proves before choosing this form
+        return barrett_u64((v + off) & M64, q, mu)
+    assert abs(vlo) < 1 << 62 and abs(vhi) < 1 << 62
+    c32 = (1 << 32) % q
+    c32s = (c32 << 64) // q
+    rlo = barrett_u64((vlo + off) & M64, q, mu)
+    rhi = barrett_u64((vhi + off) & M64, q, mu)
+    res = rlo + mulmod_shoup(rhi, c32, c32s, q)
+    return res - q if res >= q else res
+
+
+def test_integer_epilogues_against_python_integers():
+    rnd = random.Random(77)
+    amax = (1 << 31) - 1
+    for bits in (50, 51, 55, 56, 61, 62):
+        qs = [((1 << bits) - 1) | 1, (1 << (bits - 1)) + 1] + [rnd.randrange(1 << (bits - 1), 1 << bits) | 1 for _ in range(6)]
+        for q in qs:
+            for E in (7, 8):
+                cases = [[s * amax for s in signs] for signs in itertools.product((-1, 1), repeat=E)]
+                cases += [[rnd.randrange(-amax, amax + 1) for _ in range(E)] for _ in range(300)]
+                for acc in cases:
+                    want = exact(acc, q)
+                    assert reduce_int_model(acc, q, True) == want, (acc, q)
+                    if abs(sum(a << (8 * e) for e, a in enumerate(acc))) <= (1 << 62) - q:
+                        assert reduce_int_model(acc, q, False) == want, (acc, q)
+        # the one-piece form at the very edge of its precondition
+        for q in qs:
+            edge = (1 << 62) - q
+            for v in (edge, -edge, edge - 1, -edge + 1, 0, min(q, edge), -min(q, edge)):
+                acc, t = [], v
+                for e in range(7):
+                    d = ((t + 128) % 256) - 128
+                    acc.append(d)
+                    t = (t - d) >> 8
+                acc.append(t)
+                assert sum(a << (8 * e) for e, a in enumerate(acc)) == v
+                assert reduce_int_model(acc, q, False) == v % q
