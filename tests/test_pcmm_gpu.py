@@ -367,3 +367,37 @@ def test_two_plans_on_two_streams_at_once(gpu_device):
             want = pcmm_oracle(Ws[p], As[p][r], primes)
             assert (C_dev[p][r].cpu().numpy().view(np.uint64) == want).all(), (p, r)
         pkg.pcmm_plan_destroy(plans[p])
+
+
+@pytest.mark.parametrize("D", [4, 5, 6, 7])
+def test_digit_count_switches_exactly_where_the_largest_residue_stops_fitting(gpu_device, D):
+    """q - 1 + Bias_D < 256^D is the condition for D balanced digits: the largest prime below the threshold
+    256^D - Bias_D takes D digits, the smallest above it D + 1, and both products are exact at residues q - 1."""
+    import torch
+
+    import paper_2601_18511_amd as pkg
+    from oracle import pcmm_oracle
+
+    bias = sum(0x80 << (8 * i) for i in range(D))
+    T = (1 << (8 * D)) - bias                       # q <= T  <=>  q - 1 + bias < 256^D
+    below = T if T % 2 else T - 1
+    while not pi.is_prime(below):
+        below -= 2
+    above = T + 1 if T % 2 == 0 else T + 2
+    while not pi.is_prime(above):
+        above += 2
+    rng = np.random.default_rng(D)
+    M, K, Ncols = 40, 200, 70
+    W = _rand_W(rng, M, K, 8)
+    W[0, :], W[1, :] = -128, 127
+    for q, want_digits in ((below, D), (above, D + 1)):
+        bits = q.bit_length()
+        A = rng.integers(0, q, size=(1, K, Ncols), dtype=np.uint64)
+        A[0, :, 0] = q - 1
+        A[0, :, 1] = q - 2
+        A[0, ::2, 2] = q - 1
+        plan = pkg.pcmm_plan_create(torch.from_numpy(W).to(gpu_device), [q], bits, Ncols)
+        assert pkg.pcmm_plan_digits(plan) == max(want_digits, 4)
+        pkg.pcmm_plan_destroy(plan)
+        got, _ = _run_gpu(W, A, [q], bits, gpu_device)
+        assert (got == pcmm_oracle(W, A, [q])).all(), (q, want_digits)
