@@ -61,9 +61,10 @@ typedef enum {
  *   stream       hipStream_t (NULL = default stream) used for the packing kernels; this call
  *                synchronises that stream before returning
  *
- * PCMM_EUNSUPPORTED when: digits + slices - 1 > 8 (e.g. int16 W with primes above 54 bits); or one
- * limb of digit planes (about K * Ncols * digits bytes) reaches 4 GiB, or one packed W slice 2 GiB, or
- * the output has more than 2^31 tiles (of at least 32 x 32 entries each).
+ * Every combination of 24..62-bit primes with int8 or int16 weights is covered (the paper stores 16-bit
+ * weights under a modulus of about 64 bits, Section 5.3).  PCMM_EUNSUPPORTED when one limb of digit
+ * planes (about K * Ncols * digits bytes) reaches 4 GiB, or one packed W slice 2 GiB, or the output has
+ * more than 2^31 tiles (of at least 32 x 32 entries each).
  * The int32 accumulators hold a contraction over (w_bits/8)*K <= 131071; a longer K is cut into
  * ranges of 130944 (int8 W) or 65408 (int16 W) values of k, one MFMA kernel launch each, and every
  * launch after the first adds its result to C modulo q_j (the result is the same, bit for bit).

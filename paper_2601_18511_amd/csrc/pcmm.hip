@@ -40,6 +40,8 @@ struct LimbConst {
     uint64_t off;    // q * floor(2^62 / q): added to a signed value of magnitude < 2^62 to make it positive
     uint64_t c32;    // 2^32 mod q
     uint64_t c32s;   // floor(c32 * 2^64 / q)  (Shoup companion of c32)
+    uint64_t c64;    // 2^64 mod q
+    uint64_t c64s;   // floor(c64 * 2^64 / q)
     double qd;       // q as a double (exact for q < 2^53)
     double invq;     // 1.0 / q, rounded to nearest
 };
@@ -48,7 +50,7 @@ struct LimbConst {
 enum Epi : int {
     EPI_F64 = 0,     // q < 2^50: exact double-precision arithmetic (fma remainders), no 64-bit multiplies
     EPI_INT1 = 1,    // any q < 2^62, value known to fit 62 bits: one 64-bit Barrett
-    EPI_INT2 = 2,    // any q < 2^62: two Barretts and one Shoup multiplication by 2^32
+    EPI_INT2 = 2,    // any q < 2^62: one Barrett per four accumulators, joined by Shoup multiplications by 2^32, 2^64
     EPI_F64_G4 = 3,  // as EPI_F64 with the accumulators grouped in fours: |acc| < 2^28, 7 or 8 accumulators
     EPI_F64_G4P = 4  // as EPI_F64_G4 with pairs of accumulators first joined in int32: 257 |acc| < 2^31
 };
@@ -103,10 +105,11 @@ __device__ __forceinline__ int acc_read()
 template <int NACC>
 __device__ __forceinline__ void acc_declare()
 {
-    static_assert(NACC == 96 || NACC == 112 || NACC == 128 || NACC == 160, "add a clobber for this count");
+    static_assert(NACC == 96 || NACC == 112 || NACC == 128 || NACC == 144 || NACC == 160, "add a clobber for this count");
     if constexpr (NACC == 96) asm volatile("" ::: "a95");
     if constexpr (NACC == 112) asm volatile("" ::: "a111");
     if constexpr (NACC == 128) asm volatile("" ::: "a127");
+    if constexpr (NACC == 144) asm volatile("" ::: "a143");
     if constexpr (NACC == 160) asm volatile("" ::: "a159");
 }
 
@@ -551,10 +554,10 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
             } else {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    // value = vlo + 2^32 vhi with vlo, vhi of magnitude < 2^56
+                    // value = vlo + 2^32 vhi (+ 2^64 vtop for a ninth accumulator), each part of magnitude < 2^56
                     int64_t vlo = 0, vhi = 0;
 #pragma unroll
-                    for (int e = 0; e < E; ++e) {
+                    for (int e = 0; e < (E < 8 ? E : 8); ++e) {
                         int64_t v = (int64_t)avs[r][e];
                         if (e < 4) vlo += v << (8 * e);
                         else vhi += v << (8 * (e - 4));
@@ -567,6 +570,11 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
                         uint64_t rhi = barrett_u64((uint64_t)vhi + lc.off, lc.q, lc.mu);
                         res[r] = rlo + mulmod_shoup(rhi, lc.c32, lc.c32s, lc.q);
                         if (res[r] >= lc.q) res[r] -= lc.q;
+                        if constexpr (E == 9) {
+                            uint64_t rtop = barrett_u64((uint64_t)(int64_t)avs[r][8] + lc.off, lc.q, lc.mu);
+                            res[r] += mulmod_shoup(rtop, lc.c64, lc.c64s, lc.q);
+                            if (res[r] >= lc.q) res[r] -= lc.q;
+                        }
                     }
                 }
             }
@@ -751,8 +759,9 @@ hipError_t launch_gemm_ds(const pcmm_plan *p, const GemmArgs &ga, int64_t grid, 
         } else return hipErrorInvalidValue;
     } else {
         if constexpr (D >= 7) {
-            if (p->epi == EPI_INT1) hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, EPI_INT1>), g, b, 0, st, ga);
-            else hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, EPI_INT2>), g, b, 0, st, ga);
+            if (p->epi == EPI_INT2) hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, EPI_INT2>), g, b, 0, st, ga);
+            else if constexpr (D + S - 1 <= 8) hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, EPI_INT1>), g, b, 0, st, ga);
+            else return hipErrorInvalidValue;
         } else return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -784,6 +793,7 @@ hipError_t launch_gemm(const pcmm_plan *p, const GemmArgs &ga, int64_t grid, hip
         case 5: return launch_gemm_tile<5, 2>(p, ga, grid, st);
         case 6: return launch_gemm_tile<6, 2>(p, ga, grid, st);
         case 7: return launch_gemm_tile<7, 2>(p, ga, grid, st);
+        case 8: return launch_gemm_tile<8, 2>(p, ga, grid, st);
         }
     }
     return hipErrorInvalidValue;
@@ -917,7 +927,7 @@ pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncol
     if (D == 0) return PCMM_EUNSUPPORTED;
     if (D < 4) D = 4;   // kernels are built for 4..8 digits; spare top digits are zero
     const int E = D + S - 1;
-    if (E > 8) return PCMM_EUNSUPPORTED;
+    if (E > 9) return PCMM_EUNSUPPORTED;   // cannot happen with D <= 8 and S <= 2; kept as a guard
 
     pcmm_plan *p = new (std::nothrow) pcmm_plan();
     if (!p) return PCMM_ENOMEM;
@@ -995,6 +1005,8 @@ pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncol
             h[j].off = q * (uint64_t)((((u128)1) << 62) / q);
             h[j].c32 = (uint64_t)((((u128)1) << 32) % q);
             h[j].c32s = (uint64_t)(((u128)h[j].c32 << 64) / q);
+            h[j].c64 = (uint64_t)((((u128)1) << 64) % q);
+            h[j].c64s = (uint64_t)(((u128)h[j].c64 << 64) / q);
             h[j].qd = (double)q;
             h[j].invq = 1.0 / (double)q;
         }

@@ -149,7 +149,7 @@ def reduce_int_model(acc, q, two_part):
     mu = (1 << 64) // q
     off = q * ((1 << 62) // q)
     vlo = sum(a << (8 * e) for e, a in enumerate(acc[:4]))
-    vhi = sum(a << (8 * (e - 4)) for e, a in enumerate(acc) if e >= 4)
+    vhi = sum(a << (8 * (e - 4)) for e, a in enumerate(acc) if 4 <= e < 8)
     if not two_part:
         v = vlo + (vhi << 32)
         assert abs(v) <= (1 << 62) - q                         # what the plan proves before choosing this form
@@ -160,7 +160,14 @@ def reduce_int_model(acc, q, two_part):
     rlo = barrett_u64((vlo + off) & M64, q, mu)
     rhi = barrett_u64((vhi + off) & M64, q, mu)
     res = rlo + mulmod_shoup(rhi, c32, c32s, q)
-    return res - q if res >= q else res
+    res = res - q if res >= q else res
+    if len(acc) == 9:                                           # a ninth accumulator: int16 weights with 8 digits
+        c64 = (1 << 64) % q
+        c64s = (c64 << 64) // q
+        rtop = barrett_u64((acc[8] + off) & M64, q, mu)
+        res += mulmod_shoup(rtop, c64, c64s, q)
+        res = res - q if res >= q else res
+    return res
 
 
 def test_integer_epilogues_against_python_integers():
@@ -169,13 +176,13 @@ def test_integer_epilogues_against_python_integers():
     for bits in (50, 51, 55, 56, 61, 62):
         qs = [((1 << bits) - 1) | 1, (1 << (bits - 1)) + 1] + [rnd.randrange(1 << (bits - 1), 1 << bits) | 1 for _ in range(6)]
         for q in qs:
-            for E in (7, 8):
+            for E in (7, 8, 9):
                 cases = [[s * amax for s in signs] for signs in itertools.product((-1, 1), repeat=E)]
                 cases += [[rnd.randrange(-amax, amax + 1) for _ in range(E)] for _ in range(300)]
                 for acc in cases:
                     want = exact(acc, q)
                     assert reduce_int_model(acc, q, True) == want, (acc, q)
-                    if abs(sum(a << (8 * e) for e, a in enumerate(acc))) <= (1 << 62) - q:
+                    if E <= 8 and abs(sum(a << (8 * e) for e, a in enumerate(acc))) <= (1 << 62) - q:
                         assert reduce_int_model(acc, q, False) == want, (acc, q)
         # the one-piece form at the very edge of its precondition
         for q in qs:
