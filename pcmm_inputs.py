@@ -128,6 +128,8 @@ WORKLOADS = {
         Workload("ffn_up_gate", 14336, 4096, 1 << 14, 4, 36, 8),
         Workload("ffn_down", 4096, 14336, 1 << 14, 3, 36, 8),
         Workload("wide_pc_attn", 4096, 128, 1 << 16, 6, 50, 16),
+        # the paper's own storage format (Section 5.3): 16-bit weights under one modulus of about 64 bits
+        Workload("attn_proj_w16_q62", 4096, 4096, 1 << 14, 1, 62, 16),
     )
 }
 

@@ -66,9 +66,9 @@ def test_workload_shapes_match_the_llama_projection_shapes():
     assert (w["ffn_up_gate"].M, w["ffn_up_gate"].K) == (14336, 4096)
     assert (w["ffn_down"].M, w["ffn_down"].K) == (4096, 14336)
     assert (w["wide_pc_attn"].M, w["wide_pc_attn"].K, w["wide_pc_attn"].w_bits) == (4096, 128, 16)
-    assert [x.Ncols for x in w.values()] == [8192, 32768, 32768, 32768, 131072]
-    assert [x.L for x in w.values()] == [2, 4, 4, 3, 6]
-    assert [x.digits * x.slices for x in w.values()] == [5, 5, 5, 5, 14]
+    assert [x.Ncols for x in w.values()] == [8192, 32768, 32768, 32768, 131072, 32768]
+    assert [x.L for x in w.values()] == [2, 4, 4, 3, 6, 1]
+    assert [x.digits * x.slices for x in w.values()] == [5, 5, 5, 5, 14, 16]
     assert w["attn_proj"].int8_ops == 2 * 4096 * 4096 * 32768 * 4 * 5
 
 

@@ -28,7 +28,7 @@ def _slab_cols(wl):
     return list(range(64)) + list(range(N - 32, N + 32)) + list(range(wl.Ncols - 64, wl.Ncols))
 
 
-@pytest.mark.parametrize("name", ["attn_proj", "ffn_up_gate", "ffn_down", "wide_pc_attn"])
+@pytest.mark.parametrize("name", ["attn_proj", "ffn_up_gate", "ffn_down", "wide_pc_attn", "attn_proj_w16_q62"])
 def test_full_size_workload(gpu_device, name):
     import torch
 
