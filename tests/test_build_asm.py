@@ -32,7 +32,7 @@ def device_asm():
 
 
 def _kernels(asm):
-    for m in re.finditer(r"^(_ZN\S*gemm_kernel\S+):[^\n]*\n(.*?)s_endpgm", asm, re.S | re.M):
+    for m in re.finditer(r"^(_ZN\S*gemm_kernel\S+):[^\n]*\n(.*?)^\.Lfunc_end", asm, re.S | re.M):
         yield m.group(1), m.group(2).split("\n")
 
 
@@ -75,3 +75,8 @@ def test_register_budget_allows_two_workgroups_per_cu(device_asm):
     flagship = [v for k, v in found.items() if "ILi4ELi4ELi2ELi5ELi1ELi0E" in k]
     assert len(flagship) == 1
     assert flagship[0][0] == 160 and flagship[0][1] <= 256, flagship
+    # every 4-wave kernel (the ones large matrices run) fits two work-groups per CU
+    big = {k: v for k, v in found.items() if "gemm_kernelILi4E" in k}
+    assert len(big) >= 15
+    for k, (agpr, total) in big.items():
+        assert total <= 256, (k, agpr, total)
