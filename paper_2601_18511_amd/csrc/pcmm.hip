@@ -37,7 +37,7 @@ constexpr int kXcd = 8;       // accelerator complex dies, each with its own L2
 struct LimbConst {
     uint64_t q;      // the prime
     uint64_t mu;     // floor(2^64 / q)
-    uint64_t off;    // q * floor(2^62 / q): added to a signed value of magnitude < 2^62 to make it positive
+    uint64_t off;    // q * floor(2^62 / q) >= 2^61: added to a signed part of magnitude < 2^56 to make it positive
     uint64_t c32;    // 2^32 mod q
     uint64_t c32s;   // floor(c32 * 2^64 / q)  (Shoup companion of c32)
     uint64_t c64;    // 2^64 mod q
@@ -49,8 +49,8 @@ struct LimbConst {
 // How the epilogue reduces sum_e acc_e 256^e modulo q.
 enum Epi : int {
     EPI_F64 = 0,     // q < 2^50: exact double-precision arithmetic (fma remainders), no 64-bit multiplies
-    EPI_INT1 = 1,    // any q < 2^62, value known to fit 62 bits: one 64-bit Barrett
-    EPI_INT2 = 2,    // any q < 2^62: one Barrett per four accumulators, joined by Shoup multiplications by 2^32, 2^64
+    EPI_INT2 = 2,    // any q < 2^62: one 64-bit Barrett per four accumulators, joined by Shoup multiplications
+                     // by 2^32 and 2^64
     EPI_F64_G4 = 3,  // as EPI_F64 with the accumulators grouped in fours: |acc| < 2^28, 7 or 8 accumulators
     EPI_F64_G4P = 4  // as EPI_F64_G4 with pairs of accumulators first joined in int32: 257 |acc| < 2^31
 };
@@ -562,19 +562,14 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
                         if (e < 4) vlo += v << (8 * e);
                         else vhi += v << (8 * (e - 4));
                     }
-                    if constexpr (EPI == EPI_INT1) {
-                        // plan guarantees |vlo + 2^32 vhi| <= 2^62 - q, so that adding off makes it non-negative
-                        res[r] = barrett_u64((uint64_t)(vlo + (vhi << 32)) + lc.off, lc.q, lc.mu);
-                    } else {
-                        uint64_t rlo = barrett_u64((uint64_t)vlo + lc.off, lc.q, lc.mu);
-                        uint64_t rhi = barrett_u64((uint64_t)vhi + lc.off, lc.q, lc.mu);
-                        res[r] = rlo + mulmod_shoup(rhi, lc.c32, lc.c32s, lc.q);
+                    uint64_t rlo = barrett_u64((uint64_t)vlo + lc.off, lc.q, lc.mu);
+                    uint64_t rhi = barrett_u64((uint64_t)vhi + lc.off, lc.q, lc.mu);
+                    res[r] = rlo + mulmod_shoup(rhi, lc.c32, lc.c32s, lc.q);
+                    if (res[r] >= lc.q) res[r] -= lc.q;
+                    if constexpr (E == 9) {
+                        uint64_t rtop = barrett_u64((uint64_t)(int64_t)avs[r][8] + lc.off, lc.q, lc.mu);
+                        res[r] += mulmod_shoup(rtop, lc.c64, lc.c64s, lc.q);
                         if (res[r] >= lc.q) res[r] -= lc.q;
-                        if constexpr (E == 9) {
-                            uint64_t rtop = barrett_u64((uint64_t)(int64_t)avs[r][8] + lc.off, lc.q, lc.mu);
-                            res[r] += mulmod_shoup(rtop, lc.c64, lc.c64s, lc.q);
-                            if (res[r] >= lc.q) res[r] -= lc.q;
-                        }
                     }
                 }
             }
@@ -759,9 +754,7 @@ hipError_t launch_gemm_ds(const pcmm_plan *p, const GemmArgs &ga, int64_t grid, 
         } else return hipErrorInvalidValue;
     } else {
         if constexpr (D >= 7) {
-            if (p->epi == EPI_INT2) hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, EPI_INT2>), g, b, 0, st, ga);
-            else if constexpr (D + S - 1 <= 8) hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, EPI_INT1>), g, b, 0, st, ga);
-            else return hipErrorInvalidValue;
+            hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, EPI_INT2>), g, b, 0, st, ga);
         } else return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -947,25 +940,8 @@ pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncol
         return PCMM_EUNSUPPORTED;
     }
 
-    // can value = sum_e acc_e 256^e be reduced in one go?  |acc_e| <= K * sum_{s+d=e} 128 * dmax_d,
-    // dmax_d = 128 except for the top digit, which is at most top = ((qmax-1+Bias) >> 8(D-1)) - 128.
     {
-        u128 bias = 0;
-        for (int i = 0; i < D; ++i) bias |= (u128)0x80 << (8 * i);
-        int64_t top = (int64_t)((((u128)(qmax - 1) + bias) >> (8 * (D - 1))) & 0xFF) - 128;
-        if (top < 1) top = 1;
-        u128 bound = 0;
-        for (int e = 0; e < E; ++e) {
-            u128 be = 0;
-            for (int s = 0; s < S; ++s) {
-                int d = e - s;
-                if (d < 0 || d >= D) continue;
-                be += (u128)K_launch * 128 * (u128)(d == D - 1 ? top : 128);
-            }
-            bound += be << (8 * e);
-        }
-        // one Barrett needs value + off >= 0 with off = q floor(2^62 / q) > 2^62 - q
-        p->epi = qmax < ((uint64_t)1 << 50) ? EPI_F64 : (bound + qmax <= ((u128)1 << 62) ? EPI_INT1 : EPI_INT2);
+        p->epi = qmax < ((uint64_t)1 << 50) ? EPI_F64 : EPI_INT2;
         // short contractions leave small accumulators: |acc| <= S * K_launch * 2^14
         uint64_t qmin = primes_host[0];
         for (int j = 1; j < L; ++j) qmin = std::min(qmin, (uint64_t)primes_host[j]);

@@ -145,16 +145,13 @@ def mulmod_shoup(x, c, cs, q):
     return r - q if r >= q else r
 
 
-def reduce_int_model(acc, q, two_part):
+def reduce_int_model(acc, q):
     mu = (1 << 64) // q
     off = q * ((1 << 62) // q)
+    assert off >= 1 << 61
     vlo = sum(a << (8 * e) for e, a in enumerate(acc[:4]))
     vhi = sum(a << (8 * (e - 4)) for e, a in enumerate(acc) if 4 <= e < 8)
-    if not two_part:
-        v = vlo + (vhi << 32)
-        assert abs(v) <= (1 << 62) - q                         # what the plan proves before choosing this form
-        return barrett_u64((v + off) & M64, q, mu)
-    assert abs(vlo) < 1 << 62 and abs(vhi) < 1 << 62
+    assert abs(vlo) < 1 << 56 and abs(vhi) < 1 << 56
     c32 = (1 << 32) % q
     c32s = (c32 << 64) // q
     rlo = barrett_u64((vlo + off) & M64, q, mu)
@@ -180,19 +177,4 @@ def test_integer_epilogues_against_python_integers():
                 cases = [[s * amax for s in signs] for signs in itertools.product((-1, 1), repeat=E)]
                 cases += [[rnd.randrange(-amax, amax + 1) for _ in range(E)] for _ in range(300)]
                 for acc in cases:
-                    want = exact(acc, q)
-                    assert reduce_int_model(acc, q, True) == want, (acc, q)
-                    if E <= 8 and abs(sum(a << (8 * e) for e, a in enumerate(acc))) <= (1 << 62) - q:
-                        assert reduce_int_model(acc, q, False) == want, (acc, q)
-        # the one-piece form at the very edge of its precondition
-        for q in qs:
-            edge = (1 << 62) - q
-            for v in (edge, -edge, edge - 1, -edge + 1, 0, min(q, edge), -min(q, edge)):
-                acc, t = [], v
-                for e in range(7):
-                    d = ((t + 128) % 256) - 128
-                    acc.append(d)
-                    t = (t - d) >> 8
-                acc.append(t)
-                assert sum(a << (8 * e) for e, a in enumerate(acc)) == v
-                assert reduce_int_model(acc, q, False) == v % q
+                    assert reduce_int_model(acc, q) == exact(acc, q), (acc, q)
