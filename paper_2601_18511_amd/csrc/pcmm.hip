@@ -49,7 +49,7 @@ struct LimbConst {
 // How the epilogue reduces sum_e acc_e 256^e modulo q.
 enum Epi : int {
     EPI_F64 = 0,     // q < 2^50: exact double-precision arithmetic (fma remainders), no 64-bit multiplies
-    EPI_INT2 = 2,    // any q < 2^62: one 64-bit Barrett per four accumulators, joined by Shoup multiplications
+    EPI_INT = 2,    // any q < 2^62: one 64-bit Barrett per four accumulators, joined by Shoup multiplications
                      // by 2^32 and 2^64
     EPI_F64_G4 = 3,  // as EPI_F64 with the accumulators grouped in fours: |acc| < 2^28, 7 or 8 accumulators
     EPI_F64_G4P = 4  // as EPI_F64_G4 with pairs of accumulators first joined in int32: 257 |acc| < 2^31
@@ -754,7 +754,7 @@ hipError_t launch_gemm_ds(const pcmm_plan *p, const GemmArgs &ga, int64_t grid, 
         } else return hipErrorInvalidValue;
     } else {
         if constexpr (D >= 7) {
-            hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, EPI_INT2>), g, b, 0, st, ga);
+            hipLaunchKernelGGL((gemm_kernel<WM, MT, NT, D, S, EPI_INT>), g, b, 0, st, ga);
         } else return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -941,7 +941,7 @@ pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncol
     }
 
     {
-        p->epi = qmax < ((uint64_t)1 << 50) ? EPI_F64 : EPI_INT2;
+        p->epi = qmax < ((uint64_t)1 << 50) ? EPI_F64 : EPI_INT;
         // short contractions leave small accumulators: |acc| <= S * K_launch * 2^14
         uint64_t qmin = primes_host[0];
         for (int j = 1; j < L; ++j) qmin = std::min(qmin, (uint64_t)primes_host[j]);
