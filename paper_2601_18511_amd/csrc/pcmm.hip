@@ -49,8 +49,8 @@ struct LimbConst {
 // How the epilogue reduces sum_e acc_e 256^e modulo q.
 enum Epi : int {
     EPI_F64 = 0,     // q < 2^50: exact double-precision arithmetic (fma remainders), no 64-bit multiplies
-    EPI_INT = 2,    // any q < 2^62: one 64-bit Barrett per four accumulators, joined by Shoup multiplications
-                     // by 2^32 and 2^64
+    EPI_INT = 2,     // any q < 2^62: one 64-bit Barrett per four accumulators, joined by Shoup
+                     // multiplications by 2^32 and 2^64
     EPI_F64_G4 = 3,  // as EPI_F64 with the accumulators grouped in fours: |acc| < 2^28, 7 or 8 accumulators
     EPI_F64_G4P = 4  // as EPI_F64_G4 with pairs of accumulators first joined in int32: 257 |acc| < 2^31
 };
