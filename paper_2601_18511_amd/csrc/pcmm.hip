@@ -735,8 +735,8 @@ struct DevGuard {
     }
 };
 
-// Accumulator footprint limits the tile: MT*NT*E*4 accumulator registers per lane (NT = 2).
-constexpr int tile_mt(int E) { return E <= 5 ? 4 : 2; }
+// Accumulator footprint limits the tile: MT*NT*E*4 accumulator registers per lane (NT = 2), at most 160.
+constexpr int tile_mt(int E) { return E <= 5 ? 4 : (E == 6 ? 3 : 2); }
 
 template <int WM, int MT, int NT, int D, int S>
 hipError_t launch_gemm_ds(const pcmm_plan *p, const GemmArgs &ga, int64_t grid, hipStream_t st)
