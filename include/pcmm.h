@@ -74,14 +74,25 @@ pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncol
                              const uint64_t *primes_host, int32_t prime_bits, int32_t w_bits,
                              const void *W_dev, int32_t device, void *stream);
 
-/* Device bytes the plan owns (packed W + digit scratch + constants). 0 for NULL. */
+/*
+ * Device bytes the plan owns: the converted weights (1 or 2 bytes per entry of W, where the paper's
+ * converted PCMM tiles take 8, Section 5.3 and Table "model-conversion-memory"), the digit scratch of
+ * one run (digits bytes per residue of A) and the per-limb constants.  0 for NULL.
+ */
 size_t pcmm_plan_workspace_bytes(const pcmm_plan *plan);
 
-/* Number of signed 8-bit digits each residue is split into (D), 0 for NULL. */
+/*
+ * Number of signed 8-bit digits each residue is split into (D), 0 for NULL.  It follows from the size
+ * of the primes, which the paper chooses per level from its precision requirement (Section 3.1):
+ * D is the smallest count with q_max - 1 + sum_{i<D} 128*256^i < 256^D (5 for 36-bit primes, 7 for
+ * 50-bit, 8 up to 62-bit).
+ */
 int32_t pcmm_plan_digits(const pcmm_plan *plan);
 
 /*
- * One PCMM: all L limbs, all Ncols columns (both ciphertext components).
+ * One PCMM step B = W.A (Section 5.1, first paragraph) as the clear product of Section 2.2 ("PCMM from
+ * BLAS"), taken modulo every RNS prime: all L limbs, all Ncols columns (both components of the
+ * ciphertexts of Appendix A.1, which add component-wise).
  *
  *   A_dev   device, [L][K][Ncols] uint64; A_dev[j] holds residues in [0, q_j) - a caller
  *           precondition, not checked; read only
@@ -96,7 +107,7 @@ int32_t pcmm_plan_digits(const pcmm_plan *plan);
 pcmm_status pcmm_run(const pcmm_plan *plan, const uint64_t *A_dev, uint64_t *C_dev, void *stream);
 
 /*
- * Same as pcmm_run, but brackets each kernel with HIP events on `stream`, synchronises, and
+ * Same operation as pcmm_run (Section 5.1, B = W.A), but brackets each kernel with HIP events on `stream`, synchronises, and
  * reports the kernel durations in milliseconds: ms_out[0] = digit-split kernel, ms_out[1] =
  * MFMA + epilogue kernel (all its launches together when K is cut into ranges).  ms_out is a host array of 2 floats.  For measurement harnesses.
  */
@@ -108,8 +119,8 @@ pcmm_status pcmm_run_profiled(const pcmm_plan *plan, const uint64_t *A_dev, uint
  * every CU of `device` (default stream, synchronous) and reports the sustained rate in TOP/s and the
  * shader clock in MHz seen by the kernel.  random_operands != 0 fills the operand registers with
  * pseudo-random bytes, 0 with zeros: the sustainable rate depends on data toggling.  This is the
- * "MFMA-only peak on this box" that measured PCMM rates are compared with (the kernel design the paper
- * leaves open is bounded by the matrix cores; Section 2.2 only says a GPU BLAS is used).
+ * "MFMA-only peak on this box" that measured PCMM rates are compared with.  Not an operation of the
+ * paper: a measurement aid for benchmark harnesses.
  * iters: loop trips of 40 MFMAs per wave; 200000 runs for roughly 0.1 s.
  */
 pcmm_status pcmm_mfma_probe(int32_t device, int32_t iters, int32_t random_operands, double *tops_out,
@@ -140,10 +151,13 @@ pcmm_status pcmm_ring_decompose(const uint64_t *in_dev, uint64_t *out_dev, int64
 pcmm_status pcmm_ring_compose(const uint64_t *in_dev, uint64_t *out_dev, int64_t npoly, int64_t N, int64_t k,
                               int32_t device, void *stream);
 
-/* Frees everything the plan owns.  The caller makes sure no run of the plan is still in flight. */
+/*
+ * Frees everything the plan owns (the converted weights of Section 5.3, the digit scratch, the
+ * constants).  The caller makes sure no run of the plan is still in flight.  NULL is ignored.
+ */
 void pcmm_plan_destroy(pcmm_plan *plan);
 
-/* Static, human-readable name of a status code. */
+/* Static, human-readable name of a status code (library housekeeping; no counterpart in the paper). */
 const char *pcmm_status_str(pcmm_status s);
 
 #ifdef __cplusplus

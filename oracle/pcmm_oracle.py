@@ -32,7 +32,9 @@ def build_oracle(force: bool = False) -> str:
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build_oracle())
+        # PCMM_ORACLE_LIB names another build of the same pcmm_oracle.c (the sanitizer test compiles one
+        # with -fsanitize=address,undefined and runs the pins on it)
+        lib = ctypes.CDLL(os.environ.get("PCMM_ORACLE_LIB") or build_oracle())
         i64, p = ctypes.c_int64, ctypes.c_void_p
         lib.pcmm_oracle_select.argtypes = [p, p, p, i64, i64, i64, i64, p, i64, p, i64, p]
         lib.pcmm_oracle_select.restype = ctypes.c_int

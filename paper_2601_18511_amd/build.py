@@ -1,13 +1,16 @@
 """Build step: compiles csrc/pcmm.hip for gfx950 into paper_2601_18511_amd/libpcmm.so (in-tree)."""
 from __future__ import annotations
 
+import hashlib
 import os
 import subprocess
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(_HERE, "csrc", "pcmm.hip")
+HOST_HEADER = os.path.join(_HERE, "csrc", "pcmm_host.hpp")
 HEADER = os.path.join(os.path.dirname(_HERE), "include", "pcmm.h")
 LIB = os.path.join(_HERE, "libpcmm.so")
+STAMP = LIB + ".stamp"          # digest of the sources and flags the library was built from
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950",
@@ -30,18 +33,37 @@ def hipcc_path() -> str:
     return "hipcc"
 
 
+def source_digest() -> str:
+    """Digest of everything the library is built from: the sources, the headers and the flags."""
+    h = hashlib.sha256()
+    for path in (SRC, HOST_HEADER, HEADER):
+        with open(path, "rb") as f:
+            h.update(f.read())
+    h.update(" ".join(HIPCC_FLAGS).encode())
+    return h.hexdigest()
+
+
+def is_current() -> bool:
+    """True if libpcmm.so exists and was built from the sources as they are now."""
+    if not (os.path.exists(LIB) and os.path.exists(STAMP)):
+        return False
+    with open(STAMP) as f:
+        return f.read().strip() == source_digest()
+
+
 def build_library(force: bool = True) -> str:
-    """Compile the HIP library. With force=False an up-to-date libpcmm.so is kept."""
-    if not force and os.path.exists(LIB):
-        newest = max(os.path.getmtime(SRC), os.path.getmtime(HEADER))
-        if os.path.getmtime(LIB) >= newest:
-            return LIB
+    """Compile the HIP library. With force=False a libpcmm.so built from the present sources is kept."""
+    if not force and is_current():
+        return LIB
     tmp = LIB + ".tmp%d" % os.getpid()
     cmd = [hipcc_path()] + HIPCC_FLAGS + ["-o", tmp, SRC]
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if proc.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + proc.stdout)
     os.replace(tmp, LIB)
+    with open(STAMP + ".tmp%d" % os.getpid(), "w") as f:
+        f.write(source_digest() + "\n")
+    os.replace(STAMP + ".tmp%d" % os.getpid(), STAMP)
     return LIB
 
 

@@ -24,36 +24,18 @@
 #include <type_traits>
 #include <utility>
 #include "../../include/pcmm.h"
+#include "pcmm_host.hpp"
 
 namespace {
+
+using pcmm_host::LimbConst;
+using namespace pcmm_host::epi;
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 
-constexpr int kFrag = 1024;   // bytes of one 16 x 64 int8 MFMA operand fragment
+constexpr int kFrag = pcmm_host::kFragBytes;   // bytes of one 16 x 64 int8 MFMA operand fragment
 constexpr int kXcd = 8;       // accelerator complex dies, each with its own L2
-
-// Per-limb constants of the epilogue.
-struct LimbConst {
-    uint64_t q;      // the prime
-    uint64_t mu;     // floor(2^64 / q)
-    uint64_t off;    // q * floor(2^62 / q) >= 2^61: added to a signed part of magnitude < 2^56 to make it positive
-    uint64_t c32;    // 2^32 mod q
-    uint64_t c32s;   // floor(c32 * 2^64 / q)  (Shoup companion of c32)
-    uint64_t c64;    // 2^64 mod q
-    uint64_t c64s;   // floor(c64 * 2^64 / q)
-    double qd;       // q as a double (exact for q < 2^53)
-    double invq;     // 1.0 / q, rounded to nearest
-};
-
-// How the epilogue reduces sum_e acc_e 256^e modulo q.
-enum Epi : int {
-    EPI_F64 = 0,     // q < 2^50: exact double-precision arithmetic (fma remainders), no 64-bit multiplies
-    EPI_INT = 2,     // any q < 2^62: one 64-bit Barrett per four accumulators, joined by Shoup
-                     // multiplications by 2^32 and 2^64
-    EPI_F64_G4 = 3,  // as EPI_F64 with the accumulators grouped in fours: |acc| < 2^28, 7 or 8 accumulators
-    EPI_F64_G4P = 4  // as EPI_F64_G4 with pairs of accumulators first joined in int32: 257 |acc| < 2^31
-};
 
 // ------------------------------------------------------------------------------------------------
 // modular helpers (device)
@@ -389,13 +371,15 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
     const __amdgpu_buffer_rsrc_t ars =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(Adc), 0,
                                           (uint32_t)((kleft * a.ntiles - tn) * CH), 0x00020000);
-    const int w_kstride = (int)a.MB * kFrag;              // bytes between k-steps of W
-    const int a_kstride = a.ntiles * CH;                  // bytes between k-steps of the digit chunks
+    // byte offsets of a k-step: unsigned 32-bit products (one limb of digit chunks may take up to 4 GiB)
+    const uint32_t w_kstride = (uint32_t)a.MB * (uint32_t)kFrag;     // bytes between k-steps of W
+    const uint32_t a_kstride = (uint32_t)a.ntiles * (uint32_t)CH;    // bytes between k-steps of the digit chunks
     auto ld_w = [&](int sl, int wi, int kk) -> v4i {   // fragment (slice sl, row block wi, k-step kk)
-        return (v4i)__builtin_amdgcn_raw_buffer_load_b128(wrs[sl], loff, kk * w_kstride + wi * kFrag, 0);
+        return (v4i)__builtin_amdgcn_raw_buffer_load_b128(
+            wrs[sl], loff, (int)((uint32_t)kk * w_kstride + (uint32_t)(wi * kFrag)), 0);
     };
     auto ld_a = [&](uint32_t unit_off, int kk) -> v4i {   // 16 bytes of digit chunk kk
-        return (v4i)__builtin_amdgcn_raw_buffer_load_b128(ars, unit_off, kk * a_kstride, 0);
+        return (v4i)__builtin_amdgcn_raw_buffer_load_b128(ars, unit_off, (int)((uint32_t)kk * a_kstride), 0);
     };
 
     // byte offsets of this thread's 16-byte units inside a chunk (same in global memory and in LDS);
@@ -711,13 +695,12 @@ struct pcmm_plan {
     int8_t *Ad;              // device digit scratch
     LimbConst *lc;           // device
     size_t bytes;
+    size_t ad_bytes;         // size of the digit scratch one run needs
     hipEvent_t ev[4];
     bool have_ev;
 };
 
 namespace {
-
-typedef unsigned __int128 u128;
 
 struct DevGuard {
     int prev;
@@ -735,8 +718,7 @@ struct DevGuard {
     }
 };
 
-// Accumulator footprint limits the tile: MT*NT*E*4 accumulator registers per lane (NT = 2), at most 160.
-constexpr int tile_mt(int E) { return E <= 5 ? 4 : (E == 6 ? 3 : 2); }
+using pcmm_host::tile_mt;
 
 template <int WM, int MT, int NT, int D, int S>
 hipError_t launch_gemm_ds(const pcmm_plan *p, const GemmArgs &ga, int64_t grid, hipStream_t st)
@@ -792,14 +774,14 @@ hipError_t launch_gemm(const pcmm_plan *p, const GemmArgs &ga, int64_t grid, hip
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_split(const pcmm_plan *p, const uint64_t *A, hipStream_t st)
+hipError_t launch_split(const pcmm_plan *p, int8_t *Ad, const uint64_t *A, hipStream_t st)
 {
     int64_t colblocks = (p->ntiles * p->NT * 16 + 63) / 64;
     dim3 grid((unsigned)colblocks, (unsigned)p->nkb, (unsigned)p->L);
     dim3 block(256);
 #define PCMM_SPLIT_CASE(DD)                                                                              \
     case DD:                                                                                             \
-        hipLaunchKernelGGL((split_kernel<DD>), grid, block, 0, st, A, p->Ad, p->K, p->Ncols, p->nkb,     \
+        hipLaunchKernelGGL((split_kernel<DD>), grid, block, 0, st, A, Ad, p->K, p->Ncols, p->nkb,     \
                            p->ntiles, p->NT);                                                            \
         break;
     switch (p->D) {
@@ -814,21 +796,15 @@ hipError_t launch_split(const pcmm_plan *p, const uint64_t *A, hipStream_t st)
     return hipGetLastError();
 }
 
-void choose_tiles(pcmm_plan *p)
-{
-    p->NT = 2;
-    p->MT = tile_mt(p->D + p->S - 1);
-    p->WM = (p->M > (int64_t)2 * p->MT * 16) ? 4 : 2;
-}
-
-pcmm_status run_impl(const pcmm_plan *p, const uint64_t *A, uint64_t *C, hipStream_t st, float *ms)
+// Ad: the digit scratch of this run (the plan's own, or the library's static one)
+pcmm_status run_impl(const pcmm_plan *p, int8_t *Ad, const uint64_t *A, uint64_t *C, hipStream_t st, float *ms)
 {
     DevGuard dg(p->device);
     if (!dg.ok) return PCMM_EDEVICE;
 
     GemmArgs ga;
     ga.Wp = p->Wp;
-    ga.Ad = p->Ad;
+    ga.Ad = Ad;
     ga.C = C;
     ga.lc = p->lc;
     ga.M = p->M;
@@ -848,7 +824,7 @@ pcmm_status run_impl(const pcmm_plan *p, const uint64_t *A, uint64_t *C, hipStre
     const int64_t grid = ga.per_xcd * kXcd;
 
     if (ms && hipEventRecord(p->ev[0], st) != hipSuccess) return PCMM_EDEVICE;
-    if (launch_split(p, A, st) != hipSuccess) return PCMM_EDEVICE;
+    if (launch_split(p, Ad, A, st) != hipSuccess) return PCMM_EDEVICE;
     if (ms && (hipEventRecord(p->ev[1], st) != hipSuccess || hipEventRecord(p->ev[2], st) != hipSuccess))
         return PCMM_EDEVICE;
     // A contraction longer than the int32 accumulators can hold runs as several launches over
@@ -891,77 +867,27 @@ pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncol
     if (!out) return PCMM_EINVAL;
     *out = nullptr;
     if (!primes_host || !W_dev) return PCMM_EINVAL;
-    if (M <= 0 || K <= 0 || Ncols <= 0 || L <= 0 || L > 64) return PCMM_EINVAL;
-    if (M > (int64_t)1 << 24 || Ncols > (int64_t)1 << 22) return PCMM_EINVAL;   // 32-bit row offsets in the stores
-    if (w_bits != 8 && w_bits != 16) return PCMM_EINVAL;
-    if (prime_bits < 24 || prime_bits > 62) return PCMM_EINVAL;
-    if (device < 0) return PCMM_EINVAL;
-    uint64_t qmax = 0;
-    for (int j = 0; j < L; ++j) {
-        uint64_t q = primes_host[j];
-        if ((q & 1) == 0) return PCMM_EINVAL;
-        if (q <= ((uint64_t)1 << (prime_bits - 1)) || q >= ((uint64_t)1 << prime_bits)) return PCMM_EINVAL;
-        if (q > qmax) qmax = q;
-    }
-    const int S = w_bits / 8;
-    if (K > ((int64_t)1 << 22) - 128) return PCMM_EINVAL;   // k-steps are a grid dimension of the split kernel
-    // int32 headroom: one launch may contract Kl values of k with S*Kl*2^14 < 2^31, S*Kl <= 131071;
-    // in k-steps of 64, rounded down to the even count the main loop needs
-    const int64_t nkb_launch = 131071 / S / 128 * 2;
-    const int64_t K_launch = std::min(K, nkb_launch * 64);
-
-    // smallest D with (qmax - 1) + Bias_D < 256^D
-    int D = 0;
-    for (int d = 1; d <= 8; ++d) {
-        u128 bias = 0;
-        for (int i = 0; i < d; ++i) bias |= (u128)0x80 << (8 * i);
-        if ((u128)(qmax - 1) + bias < ((u128)1 << (8 * d))) { D = d; break; }
-    }
-    if (D == 0) return PCMM_EUNSUPPORTED;
-    if (D < 4) D = 4;   // kernels are built for 4..8 digits; spare top digits are zero
-    const int E = D + S - 1;
-    if (E > 9) return PCMM_EUNSUPPORTED;   // cannot happen with D <= 8 and S <= 2; kept as a guard
+    pcmm_host::Geometry g;
+    const pcmm_status grc = pcmm_host::plan_geometry(M, K, Ncols, L, primes_host, prime_bits, w_bits, device, &g);
+    if (grc != PCMM_OK) return grc;
+    const int D = g.D, S = g.S;
 
     pcmm_plan *p = new (std::nothrow) pcmm_plan();
     if (!p) return PCMM_ENOMEM;
     p->M = M; p->K = K; p->Ncols = Ncols; p->L = L;
     p->prime_bits = prime_bits; p->w_bits = w_bits; p->device = device;
     p->D = D; p->S = S;
+    p->WM = g.WM; p->MT = g.MT; p->NT = g.NT;
+    p->epi = g.epi;
+    p->MB = g.MB; p->nkb = g.nkb; p->mtiles = g.mtiles; p->ntiles = g.ntiles;
+    p->nkb_launch = g.nkb_launch;
     p->Wp = nullptr; p->Ad = nullptr; p->lc = nullptr; p->bytes = 0; p->have_ev = false;
-    choose_tiles(p);
-    const int64_t BM = (int64_t)p->WM * p->MT * 16, BN = (int64_t)p->NT * 16;
-    p->mtiles = (M + BM - 1) / BM;
-    p->ntiles = (Ncols + BN - 1) / BN;
-    p->MB = p->mtiles * BM / 16;
-    p->nkb = (K + 127) / 128 * 2;   // the main loop takes two k-steps of 64 per round
-    p->nkb_launch = nkb_launch;
-    if ((int64_t)L * p->mtiles * p->ntiles > 0x7fffff00LL) {   // one work-group per tile: the grid is a 32-bit count
-        delete p;
-        return PCMM_EUNSUPPORTED;
-    }
-
-    {
-        p->epi = qmax < ((uint64_t)1 << 50) ? EPI_F64 : EPI_INT;
-        // short contractions leave small accumulators: |acc| <= S * K_launch * 2^14
-        uint64_t qmin = primes_host[0];
-        for (int j = 1; j < L; ++j) qmin = std::min(qmin, (uint64_t)primes_host[j]);
-        if (p->epi == EPI_F64 && E >= 7 && qmin > ((uint64_t)1 << 37)) {
-            if ((int64_t)S * K_launch <= 509) p->epi = EPI_F64_G4P;   // 257 * S*K * 2^14 < 2^31
-            else if ((int64_t)S * K_launch <= 16383) p->epi = EPI_F64_G4;
-        }
-    }
 
     DevGuard dg(device);
     if (!dg.ok) { delete p; return PCMM_EDEVICE; }
     hipStream_t st = (hipStream_t)stream;
 
-    const size_t wp_bytes = (size_t)S * p->MB * p->nkb * kFrag;
-    const size_t ad_bytes = (size_t)L * p->ntiles * p->nkb * p->NT * D * kFrag;
-    // buffer loads address one W slice and one limb of digit planes with 32-bit offsets
-    if (wp_bytes / S >= ((size_t)1 << 31) || ad_bytes / L >= ((size_t)1 << 32)) {
-        delete p;
-        return PCMM_EUNSUPPORTED;
-    }
+    const size_t wp_bytes = g.wp_bytes, ad_bytes = g.ad_bytes;
     const size_t lc_bytes = (size_t)L * sizeof(LimbConst);
     int *err_dev = nullptr;
     pcmm_status rc = PCMM_OK;
@@ -971,21 +897,11 @@ pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncol
         rc = PCMM_ENOMEM;
     }
     p->bytes = wp_bytes + ad_bytes + lc_bytes;
+    p->ad_bytes = ad_bytes;
 
     if (rc == PCMM_OK) {
-        LimbConst h[64];
-        for (int j = 0; j < L; ++j) {
-            uint64_t q = primes_host[j];
-            h[j].q = q;
-            h[j].mu = (uint64_t)((((u128)1) << 64) / q);
-            h[j].off = q * (uint64_t)((((u128)1) << 62) / q);
-            h[j].c32 = (uint64_t)((((u128)1) << 32) % q);
-            h[j].c32s = (uint64_t)(((u128)h[j].c32 << 64) / q);
-            h[j].c64 = (uint64_t)((((u128)1) << 64) % q);
-            h[j].c64s = (uint64_t)(((u128)h[j].c64 << 64) / q);
-            h[j].qd = (double)q;
-            h[j].invq = 1.0 / (double)q;
-        }
+        LimbConst h[pcmm_host::kMaxLimbs];
+        for (int j = 0; j < L; ++j) h[j] = pcmm_host::limb_const(primes_host[j]);
         if (hipMemcpyAsync(p->lc, h, lc_bytes, hipMemcpyHostToDevice, st) != hipSuccess ||
             hipMemsetAsync(err_dev, 0, sizeof(int), st) != hipSuccess ||
             hipStreamSynchronize(st) != hipSuccess)   // h lives on this stack frame
@@ -1037,14 +953,14 @@ int32_t pcmm_plan_digits(const pcmm_plan *plan) { return plan ? plan->D : 0; }
 pcmm_status pcmm_run(const pcmm_plan *plan, const uint64_t *A_dev, uint64_t *C_dev, void *stream)
 {
     if (!plan || !A_dev || !C_dev) return PCMM_EINVAL;
-    return run_impl(plan, A_dev, C_dev, (hipStream_t)stream, nullptr);
+    return run_impl(plan, plan->Ad, A_dev, C_dev, (hipStream_t)stream, nullptr);
 }
 
 pcmm_status pcmm_run_profiled(const pcmm_plan *plan, const uint64_t *A_dev, uint64_t *C_dev, void *stream,
                               float *ms_out)
 {
     if (!plan || !A_dev || !C_dev || !ms_out) return PCMM_EINVAL;
-    return run_impl(plan, A_dev, C_dev, (hipStream_t)stream, ms_out);
+    return run_impl(plan, plan->Ad, A_dev, C_dev, (hipStream_t)stream, ms_out);
 }
 
 pcmm_status pcmm_mfma_probe(int32_t device, int32_t iters, int32_t random_operands, double *tops_out,

@@ -37,12 +37,12 @@ class PcmmError(RuntimeError):
 
 
 def load_library() -> ctypes.CDLL:
-    """Load libpcmm.so (building it first only if no built library exists)."""
+    """Load libpcmm.so; it is built first if there is none or if it was built from other sources than the
+    present ones (a stale binary must not pass for the code under test)."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.LIB):
-        _build.build_library(force=True)
+    _build.build_library(force=False)
     lib = ctypes.CDLL(_build.LIB)
     vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
     lib.pcmm_plan_create.argtypes = [ctypes.POINTER(vp), i64, i64, i64, i32, vp, i32, i32, vp, i32, vp]

@@ -41,14 +41,14 @@ def test_decompose_and_compose_match_the_oracle(gpu_device, npoly, N, k):
 
 
 def test_full_size_batch_round_trip_and_samples(gpu_device):
-    """The batch bench.py times: 4 limbs x 2 components x 128 ciphertexts over R_{2^16}, k = 16.  Sampled
+    """The batch bench.py times: 4 limbs x 2 components x 512 ciphertexts over R_{2^16}, k = 16.  Sampled
     polynomials against the oracle, the whole batch by the round trip compose(decompose(p)) = p."""
     import torch
 
     import paper_2601_18511_amd as pkg
     from oracle import ring_decompose
 
-    npoly, N, k = 4 * 2 * 128, 1 << 16, 16
+    npoly, N, k = 4 * 2 * 512, 1 << 16, 16
     g = torch.Generator(device=gpu_device)
     g.manual_seed(5)
     p = torch.randint(-(1 << 62), 1 << 62, (npoly, N), dtype=torch.int64, device=gpu_device, generator=g)
