@@ -8,6 +8,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(_HERE, "csrc", "pcmm.hip")
 HOST_HEADER = os.path.join(_HERE, "csrc", "pcmm_host.hpp")
+DEVICE_HEADER = os.path.join(_HERE, "csrc", "pcmm_device.hpp")
 HEADER = os.path.join(os.path.dirname(_HERE), "include", "pcmm.h")
 LIB = os.path.join(_HERE, "libpcmm.so")
 STAMP = LIB + ".stamp"          # digest of the sources and flags the library was built from
@@ -36,7 +37,7 @@ def hipcc_path() -> str:
 def source_digest() -> str:
     """Digest of everything the library is built from: the sources, the headers and the flags."""
     h = hashlib.sha256()
-    for path in (SRC, HOST_HEADER, HEADER):
+    for path in (SRC, HOST_HEADER, DEVICE_HEADER, HEADER):
         with open(path, "rb") as f:
             h.update(f.read())
     h.update(" ".join(HIPCC_FLAGS).encode())
