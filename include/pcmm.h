@@ -115,6 +115,23 @@ pcmm_status pcmm_run_profiled(const pcmm_plan *plan, const uint64_t *A_dev, uint
                               void *stream, float *ms_out);
 
 /*
+ * pcmm_run for callers that cannot allocate device memory and want none allocated on their behalf
+ * while they run: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same result (bit for bit) and same asynchrony as pcmm_run, but the digit planes of
+ * A go to a buffer of PCMM_NOALLOC_SCRATCH_BYTES that is part of the library's device image (every
+ * GPU the library runs on holds it until the process ends), not to the plan's own scratch.  The call
+ * allocates and frees nothing, on the host or on the device.
+ *
+ * PCMM_EUNSUPPORTED if the plan's digit planes, L * ceil(K/128)*128 * ceil(Ncols/32)*32 * digits
+ * bytes, exceed PCMM_NOALLOC_SCRATCH_BYTES; nothing is enqueued then.
+ * All calls on one GPU share that GPU's buffer, whatever their plans: two calls that overlap in time
+ * on one GPU (different streams, or threads) race.  Nothing is kept in the buffer between calls and
+ * nothing in it has to be cleared: every call first rewrites all the bytes it later reads.
+ */
+#define PCMM_NOALLOC_SCRATCH_BYTES (64u << 20)
+pcmm_status pcmm_run_noalloc(const pcmm_plan *plan, const uint64_t *A_dev, uint64_t *C_dev, void *stream);
+
+/*
  * Measurement aid: runs a register-resident loop of v_mfma_i32_16x16x64_i8 with no memory traffic on
  * every CU of `device` (default stream, synchronous) and reports the sustained rate in TOP/s and the
  * shader clock in MHz seen by the kernel.  random_operands != 0 fills the operand registers with

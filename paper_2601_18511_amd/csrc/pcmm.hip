@@ -20,6 +20,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <type_traits>
 #include <utility>
@@ -560,6 +561,14 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(long long *out, int ite
 }  // namespace
 
 // ------------------------------------------------------------------------------------------------
+// static digit scratch for pcmm_run_noalloc
+// ------------------------------------------------------------------------------------------------
+// Every GPU the library runs on holds its own copy of this array until the process ends.  Host code
+// never passes the array's name to a kernel or a HIP call: it asks HIP for the device address once per
+// device (static_scratch_ptr) and uses that pointer from then on.
+static __device__ __align__(256) unsigned char scratch[PCMM_NOALLOC_SCRATCH_BYTES];
+
+// ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
 struct pcmm_plan {
@@ -598,6 +607,27 @@ struct DevGuard {
 };
 
 using pcmm_host::tile_mt;
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each device, nullptr until asked for
+
+// Device address of this device's copy of `scratch`; `device` must be the current device.
+// nullptr if HIP cannot tell.
+int8_t *static_scratch_ptr(int device)
+{
+    if (device < 0 || device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[device] = ptr;
+    }
+    return static_cast<int8_t *>(g_scratch_ptr[device]);
+}
 
 template <int WM, int MT, int NT, int D, int S>
 hipError_t launch_gemm_ds(const pcmm_plan *p, const GemmArgs &ga, int64_t grid, hipStream_t st)
@@ -765,6 +795,8 @@ pcmm_status pcmm_plan_create(pcmm_plan **out, int64_t M, int64_t K, int64_t Ncol
     DevGuard dg(device);
     if (!dg.ok) { delete p; return PCMM_EDEVICE; }
     hipStream_t st = (hipStream_t)stream;
+    // set-up for pcmm_run_noalloc: this device's address of the static digit scratch, asked for once
+    if (!static_scratch_ptr(device)) { delete p; return PCMM_EDEVICE; }
 
     const size_t wp_bytes = g.wp_bytes, ad_bytes = g.ad_bytes;
     const size_t lc_bytes = (size_t)L * sizeof(LimbConst);
@@ -840,6 +872,22 @@ pcmm_status pcmm_run_profiled(const pcmm_plan *plan, const uint64_t *A_dev, uint
 {
     if (!plan || !A_dev || !C_dev || !ms_out) return PCMM_EINVAL;
     return run_impl(plan, plan->Ad, A_dev, C_dev, (hipStream_t)stream, ms_out);
+}
+
+pcmm_status pcmm_run_noalloc(const pcmm_plan *plan, const uint64_t *A_dev, uint64_t *C_dev, void *stream)
+{
+    if (!plan || !A_dev || !C_dev) return PCMM_EINVAL;
+    if (plan->ad_bytes > (size_t)PCMM_NOALLOC_SCRATCH_BYTES) return PCMM_EUNSUPPORTED;
+    int8_t *ptr;
+    {
+        DevGuard dg(plan->device);
+        if (!dg.ok) return PCMM_EDEVICE;
+        ptr = static_scratch_ptr(plan->device);   // resolved by pcmm_plan_create; a table look-up here
+    }
+    if (!ptr) return PCMM_EDEVICE;
+    // the digit split rewrites every byte of the scratch that the MFMA kernel reads, so nothing has to
+    // start at zero
+    return run_impl(plan, ptr, A_dev, C_dev, (hipStream_t)stream, nullptr);
 }
 
 pcmm_status pcmm_mfma_probe(int32_t device, int32_t iters, int32_t random_operands, double *tops_out,

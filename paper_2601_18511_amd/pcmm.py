@@ -20,6 +20,7 @@ EXPORTED = (
     "pcmm_plan_digits",
     "pcmm_run",
     "pcmm_run_profiled",
+    "pcmm_run_noalloc",
     "pcmm_plan_destroy",
     "pcmm_status_str",
     "pcmm_mfma_probe",
@@ -53,6 +54,8 @@ def load_library() -> ctypes.CDLL:
     lib.pcmm_plan_digits.restype = i32
     lib.pcmm_run.argtypes = [vp, vp, vp, vp]
     lib.pcmm_run.restype = ctypes.c_int
+    lib.pcmm_run_noalloc.argtypes = [vp, vp, vp, vp]
+    lib.pcmm_run_noalloc.restype = ctypes.c_int
     lib.pcmm_run_profiled.argtypes = [vp, vp, vp, vp, ctypes.POINTER(ctypes.c_float)]
     lib.pcmm_run_profiled.restype = ctypes.c_int
     lib.pcmm_mfma_probe.argtypes = [i32, i32, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
@@ -141,6 +144,18 @@ def pcmm_run(plan: PcmmPlan, A: torch.Tensor, C: torch.Tensor, stream=None) -> N
         rc = load_library().pcmm_run(plan.handle, A.data_ptr(), C.data_ptr(), _stream_handle(stream))
     if rc != PCMM_OK:
         raise PcmmError(rc, "pcmm_run")
+
+
+NOALLOC_SCRATCH_BYTES = 64 << 20     # PCMM_NOALLOC_SCRATCH_BYTES of include/pcmm.h
+
+
+def pcmm_run_noalloc(plan: PcmmPlan, A: torch.Tensor, C: torch.Tensor, stream=None) -> None:
+    """pcmm_run through the library's static digit scratch: the call allocates nothing. Asynchronous."""
+    _check_io(plan, A, C)
+    with torch.cuda.device(plan.device):
+        rc = load_library().pcmm_run_noalloc(plan.handle, A.data_ptr(), C.data_ptr(), _stream_handle(stream))
+    if rc != PCMM_OK:
+        raise PcmmError(rc, "pcmm_run_noalloc")
 
 
 def pcmm_run_profiled(plan: PcmmPlan, A: torch.Tensor, C: torch.Tensor, stream=None):
