@@ -1,15 +1,18 @@
-"""Build step: compiles csrc/pcmm.hip for gfx950 into paper_2601_18511_amd/libpcmm.so (in-tree)."""
+"""Build step: compiles csrc/*.hip for gfx950 into paper_2601_18511_amd/libpcmm.so (in-tree)."""
 from __future__ import annotations
 
 import hashlib
 import os
 import subprocess
+import tempfile
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(_HERE, "csrc", "pcmm.hip")
-HOST_HEADER = os.path.join(_HERE, "csrc", "pcmm_host.hpp")
-DEVICE_HEADER = os.path.join(_HERE, "csrc", "pcmm_device.hpp")
+CSRC = os.path.join(_HERE, "csrc")
+# translation units of the library (each holds its own kernels; no device code crosses files)
+SOURCES = [os.path.join(CSRC, "pcmm.hip"), os.path.join(CSRC, "pcmm_shortk.hip")]
+SRC = SOURCES[0]
 HEADER = os.path.join(os.path.dirname(_HERE), "include", "pcmm.h")
+INTERNAL_HEADERS = [os.path.join(CSRC, n) for n in ("pcmm_host.hpp", "pcmm_device.hpp", "pcmm_shortk.hpp")]
 LIB = os.path.join(_HERE, "libpcmm.so")
 STAMP = LIB + ".stamp"          # digest of the sources and flags the library was built from
 
@@ -18,7 +21,6 @@ HIPCC_FLAGS = [
     "-O3",
     "-std=c++17",
     "-fPIC",
-    "-shared",
     "-Wall",
     # the epilogue relies on exactly the double-precision operations it spells out
     "-ffp-contract=off",
@@ -37,7 +39,7 @@ def hipcc_path() -> str:
 def source_digest() -> str:
     """Digest of everything the library is built from: the sources, the headers and the flags."""
     h = hashlib.sha256()
-    for path in (SRC, HOST_HEADER, DEVICE_HEADER, HEADER):
+    for path in SOURCES + INTERNAL_HEADERS + [HEADER]:
         with open(path, "rb") as f:
             h.update(f.read())
     h.update(" ".join(HIPCC_FLAGS).encode())
@@ -56,11 +58,23 @@ def build_library(force: bool = True) -> str:
     """Compile the HIP library. With force=False a libpcmm.so built from the present sources is kept."""
     if not force and is_current():
         return LIB
-    tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [hipcc_path()] + HIPCC_FLAGS + ["-o", tmp, SRC]
-    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if proc.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + proc.stdout)
+    hipcc = hipcc_path()
+    with tempfile.TemporaryDirectory(prefix="pcmm_build_") as tmpdir:
+        objs, procs = [], []
+        for src in SOURCES:      # the translation units compile side by side
+            obj = os.path.join(tmpdir, os.path.basename(src) + ".o")
+            objs.append(obj)
+            procs.append((src, subprocess.Popen([hipcc] + HIPCC_FLAGS + ["-c", "-o", obj, src],
+                                                stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+        for src, proc in procs:
+            out, _ = proc.communicate()
+            if proc.returncode != 0:
+                raise RuntimeError("hipcc failed on %s:\n%s" % (src, out))
+        tmp = LIB + ".tmp%d" % os.getpid()
+        proc = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs,
+                              stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if proc.returncode != 0:
+            raise RuntimeError("hipcc failed to link:\n" + proc.stdout)
     os.replace(tmp, LIB)
     with open(STAMP + ".tmp%d" % os.getpid(), "w") as f:
         f.write(source_digest() + "\n")

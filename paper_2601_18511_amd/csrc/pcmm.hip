@@ -27,6 +27,7 @@
 #include "../../include/pcmm.h"
 #include "pcmm_host.hpp"
 #include "pcmm_device.hpp"
+#include "pcmm_shortk.hpp"
 
 using namespace pcmm_device;
 
@@ -736,6 +737,14 @@ pcmm_status run_impl(const pcmm_plan *p, int8_t *Ad, const uint64_t *A, uint64_t
     if (launch_split(p, Ad, A, st) != hipSuccess) return PCMM_EDEVICE;
     if (ms && (hipEventRecord(p->ev[1], st) != hipSuccess || hipEventRecord(p->ev[2], st) != hipSuccess))
         return PCMM_EDEVICE;
+    if (pcmm_shortk::covers(p->D, p->S, p->epi, p->nkb)) {
+        // at most 128 values of k: the kernel that keeps the digit fragments in registers and walks down W
+        pcmm_shortk::Args sa;
+        sa.Wp = p->Wp; sa.Ad = Ad; sa.C = C; sa.lc = p->lc;
+        sa.M = p->M; sa.Ncols = p->Ncols; sa.MB = p->MB;
+        sa.ntiles = (int)p->ntiles; sa.L = p->L;
+        if (pcmm_shortk::launch(sa, p->D, p->S, p->epi, st) != hipSuccess) return PCMM_EDEVICE;
+    } else
     // A contraction longer than the int32 accumulators can hold runs as several launches over
     // consecutive ranges of k; every launch after the first adds its result to C modulo q_j.
     for (int64_t kb0 = 0; kb0 < p->nkb; kb0 += p->nkb_launch) {

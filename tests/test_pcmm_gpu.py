@@ -84,6 +84,38 @@ def test_random_shapes_bit_exact(gpu_device, M, K, Ncols, bits, L, wbits):
     assert (got == want).all(), int((got != want).sum())
 
 
+@pytest.mark.parametrize(
+    "M,K,Ncols,bits,L,wbits",
+    [
+        # contractions of at most 128 values of k take the kernel that keeps the digit fragments in
+        # registers and walks down W in stages of 64 rows; 64-column strips, one wave per 16 columns
+        (1000, 128, 64, 50, 2, 16),       # few strips: the rows are cut into several work-groups
+        (1000, 128, 130, 36, 1, 8),       # an odd number of 32-column tiles: half a strip lies in the padding
+        (65, 97, 1100, 50, 3, 16),        # one row past a stage; K tail inside the second k-step
+        (63, 64, 17, 50, 2, 16),          # one k-step of real data, the second all padding
+        (4096, 128, 96, 50, 1, 16),       # as many rows as the wide workload
+        (200, 128, 300, 44, 2, 16),       # 6 digits x 2 slices: 7 accumulators, groups of three (q < 2^37 fails the G4 bound)
+        (200, 100, 300, 49, 2, 8),        # 7 digits, 1 slice
+        (129, 128, 200, 28, 2, 16),       # 4 digits, 2 slices
+        (300, 33, 70, 40, 2, 8),          # 5 digits under a 40-bit prime
+        (100, 128, 48, 41, 2, 16),        # 6 digits
+    ],
+)
+def test_short_contractions_bit_exact(gpu_device, M, K, Ncols, bits, L, wbits):
+    from oracle import pcmm_oracle
+
+    rng = np.random.default_rng(M * 77 + K + Ncols)
+    primes = pi.ntt_primes(bits, 1 << 10, L)
+    W = _rand_W(rng, M, K, wbits)
+    W[0, :] = -128 if wbits == 8 else -32768
+    W[M - 1, :] = 127 if wbits == 8 else 32639
+    A = _rand_A(rng, K, Ncols, primes)
+    A[:, :, 0] = np.array(primes, dtype=np.uint64)[:, None] - np.uint64(1)
+    got, _ = _run_gpu(W, A, primes, bits, gpu_device)
+    want = pcmm_oracle(W, A, primes)
+    assert (got == want).all(), int((got != want).sum())
+
+
 def _digit_pattern_residues(q, bits, K, Ncols, rng):
     """Residues whose balanced base-256 digits sit at the extremes (+127 / -128 / 0 / -1 patterns)."""
     pats = []
@@ -103,7 +135,7 @@ def _digit_pattern_residues(q, bits, K, Ncols, rng):
                                           # the short-contraction epilogues and the sizes where they switch
                                           (50, 16, 254), (50, 16, 255), (50, 8, 509), (50, 8, 510),
                                           (50, 16, 8191), (50, 16, 8192), (50, 8, 16383), (50, 8, 16384),
-                                          (40, 16, 200), (44, 16, 3000), (38, 16, 100),
+                                          (40, 16, 200), (44, 16, 3000), (38, 16, 100), (50, 16, 128), (36, 8, 128), (49, 8, 64),
                                           (62, 16, 2048), (62, 16, 65535), (58, 16, 700)])
 def test_adversarial_extremes_and_int32_headroom(gpu_device, bits, wbits, K):
     """All-(-128) / all-127 weight rows against extreme digit patterns: the int32 accumulators reach
