@@ -9,12 +9,16 @@
 // 16 bytes) in registers for the whole kernel: the digit planes are read from memory exactly once.
 // The work-group then walks down the rows of W.  W is shared by the four waves, so it is staged through
 // LDS, four 16-row blocks at a time, double-buffered: the global loads of stage s+2 are issued before
-// the stores of stage s+1's results, so that waiting for them (the memory counter is in order) never
-// waits for a store.  Per 16 x 16 output block a wave issues 2 D S MFMAs into E = D+S-1 accumulators
-// (ordinary vector registers here: the compiler tracks the MFMA hazards, and the epilogue reads them
-// without accumulator-register moves), and reduces the previous block's accumulators while they run:
-// two accumulator sets alternate, so every iteration holds one block of matrix work and one block of
-// vector work that do not depend on each other.
+// the results of stage s+1 are stored.  Per 16 x 16 output block a wave issues 2 D S MFMAs into
+// E = D+S-1 accumulators (ordinary vector registers here: the compiler tracks the MFMA hazards, and the
+// epilogue reads them without accumulator-register moves), reduces them and stores the block.  The
+// kernel fits 128 registers per lane for most digit counts, so four waves share a SIMD: while one reduces and stores its
+// block, the others keep the matrix cores busy.  (A variant that kept two accumulator sets per wave and
+// interleaved the reduction of one block with the MFMAs of the next, at two waves per SIMD, measured
+// 6 % slower; a fifth wave per work-group that does nothing but the W loads, 15 % slower.)
+// Measured on the 4096 x 128 by 128 x 131072 case: the chip is power-limited here (shader clock about
+// 1.5 GHz with matrix cores, double-precision vector work and 4 TB/s of stores all active); the output
+// stores alone, in this pattern or any other, take 4.6 ms of the 6.0 ms.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <algorithm>
@@ -39,7 +43,7 @@ struct KArgs {
 
 // MODE: the grouping reduce_f64 uses (0: groups of three accumulators; 2: groups of four, pairs joined in int32)
 template <int D, int S, int MODE>
-__global__ __launch_bounds__(256, 2) void gemm_shortk_kernel(KArgs ka)
+__global__ __launch_bounds__(256, 3) void gemm_shortk_kernel(KArgs ka)
 {
     constexpr int E = D + S - 1;
     constexpr int CH = 2 * D * kFrag;             // one 32-column digit chunk of one k-step
@@ -150,8 +154,7 @@ __global__ __launch_bounds__(256, 2) void gemm_shortk_kernel(KArgs ka)
     // reduce and store one block.  Accumulator register r of lane l is output row 4*(l/16)+r, column l%16.
     // Rows at or beyond M fall outside the buffer descriptor and are dropped by its range check.
     auto emit = [&](const v4i (&acc)[E], int mb) {
-        // no branch here: a block beyond M gets an empty descriptor, so that the matrix work of the next
-        // block and this vector work stay in one basic block for the scheduler to interleave
+        // no branch here: a block beyond M gets an empty descriptor, which drops its stores
         const int64_t m0 = min((int64_t)mb * 16, a.M);
         const uint32_t rows_valid = (uint32_t)min((int64_t)16, a.M - m0);
         const __amdgpu_buffer_rsrc_t crs =
@@ -165,35 +168,31 @@ __global__ __launch_bounds__(256, 2) void gemm_shortk_kernel(KArgs ka)
         reduce_f64<E, MODE, 4>(avs, lc.qd, lc.invq, res);
 #pragma unroll
         for (int r = 0; r < 4; ++r)
+            // non-temporal: the output is written once and not read back by this kernel
             __builtin_amdgcn_raw_buffer_store_b64((v2u){(uint32_t)res[r], (uint32_t)(res[r] >> 32)}, crs,
-                                                  c_lane + (uint32_t)r * c_rowbytes, 0, 0);
+                                                  c_lane + (uint32_t)r * c_rowbytes, 0, 2);
     };
 
-    // ---- pipeline.  Entering stage s: LDS[s&1] holds stage s, wst holds stage s+1 (if any), accA holds
-    // the finished block 0 of stage s.
+    // ---- stage s is in LDS[s & 1] while stage s+1 travels global -> registers
     const int nst = ka.stages_per_part;
-    v4i accA[E], accB[E];
+    v4i acc[E];
     stage_load(0);
     stage_store(0);
     __syncthreads();
     if (nst > 1) stage_load(1);
-    compute(accA, 0, 0);
     for (int s = 0; s < nst; ++s) {
         const int cur = s & 1;
         const int mb0 = mb_first + s * RS;
-        compute(accB, cur, 1);
-        emit(accA, mb0 + 0);
-        compute(accA, cur, 2);
-        emit(accB, mb0 + 1);
-        compute(accB, cur, 3);
-        emit(accA, mb0 + 2);
+#pragma unroll
+        for (int r = 0; r < RS; ++r) {
+            compute(acc, cur, r);
+            emit(acc, mb0 + r);
+        }
         if (s + 1 < nst) {
-            stage_store(cur ^ 1);            // stage s+1: every wave has left the buffer (barrier of stage s-1)
+            stage_store(cur ^ 1);            // every wave has left that buffer (barrier of stage s-1)
             __syncthreads();
             if (s + 2 < nst) stage_load(s + 2);
-            compute(accA, cur ^ 1, 0);
         }
-        emit(accB, mb0 + 3);
     }
 }
 
