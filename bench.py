@@ -126,6 +126,31 @@ def ring_switch_rates(pkg, torch, dev, copy_GBs: float, iters: int = 10):
     return out
 
 
+def slot_rearrange_rates(pkg, torch, dev, copy_GBs: float, iters: int = 10):
+    """The run-time plaintext rearrangement of the slot-encoded PCMM of PC-attention (not part of the timed step):
+    d = 128 (the head dimension), 64 stored matrices, all d rearranged plaintexts of each per call (b = 16)."""
+    d, b, ell, batch = 128, 16, 1, 64
+    S = torch.randint(0, 1 << 62, (batch, d, d), dtype=torch.int64, device=dev)
+    out = torch.empty((batch, d, d, d), dtype=torch.int64, device=dev)
+    stream = torch.cuda.current_stream()
+    pkg.pcmm_slot_rearrange(S, out, d, ell, b, 0, d, stream)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(iters):
+        pkg.pcmm_slot_rearrange(S, out, d, ell, b, 0, d, stream)
+    e1.record(stream)
+    e1.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    nbytes = 8.0 * batch * d * d * (1 + d)            # S read once, every plaintext written once
+    k = 37
+    r = torch.arange(d, device=dev)
+    want = S[:, (r[:, None] - ell * k - (k // b) * b) % d, (r[None, :] + k) % d]
+    return {"workload": "%d stored %dx%d matrices -> %d rearranged plaintexts each (b = %d, l = %d), uint64" % (batch, d, d, d, b, ell),
+            "algorithmic_bytes": nbytes, "ms": ms, "GBs": nbytes / (ms * 1e-3) / 1e9,
+            "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "frac_of_copy": nbytes / (ms * 1e-3) / 1e9 / copy_GBs,
+            "sample_matches_index_formula": bool(torch.equal(out[:, k], want))}
+
+
 def library_int8_gemm(torch, dev, wl, iters: int = 5):
     """Context only: the vendor library's plain int8 GEMM (torch._int_mm) on the raw int8 products of the same
     workload, W[M][K] x digit planes [K][Ncols*L*D] -> int32, random int8 data.  No digit split, no recombination,
@@ -246,7 +271,8 @@ def main() -> int:
     ap.add_argument("--only", action="store_true", help="measure the headline workload only, not the others")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip every oracle run (no row check either)")
     ap.add_argument("--no-ring-switch", action="store_true",
-                    help="skip the (untimed-step) measurement of the ring-switch permutation kernels")
+                    help="skip the (untimed-step) measurements of the permutation kernels beside the PCMM: ring switching "
+                         "and the slot-encoded PCMM's plaintext rearrangement")
     ap.add_argument("--no-library-gemm", action="store_true",
                     help="skip timing the vendor library's plain int8 GEMM on the same int8 work (context only)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -342,6 +368,7 @@ def main() -> int:
         result["all_gpu_rows_match_oracle"] = ok
     if not args.no_ring_switch:
         result["ring_switch"] = ring_switch_rates(pkg, torch, dev, copy_GBs)
+        result["slot_rearrange"] = slot_rearrange_rates(pkg, torch, dev, copy_GBs)
     if not args.no_library_gemm:
         result["library_int8_gemm"] = library_int8_gemm(torch, dev, head)
     print(json.dumps(result))

@@ -169,6 +169,36 @@ pcmm_status pcmm_ring_compose(const uint64_t *in_dev, uint64_t *out_dev, int64_t
                               int32_t device, void *stream);
 
 /*
+ * Run-time plaintext rearrangement of the slot-encoded batch PCMM of PC-attention (Section 4.2, Eq. "pcmm";
+ * Appendix E, Theorem 1).  For d x d matrices stored row after row, the depth-one PCMM needs, for every
+ * baby step i < b and giant step j < g = d / b, the plaintext
+ *
+ *     pt_{A,i,j,l} = rot_R^{-l (i + j b) - j b} o rot_C^{i + j b}( S ) ,    S = tau^l o sigma(pt_A),
+ *
+ * where rot_C^k(M)[r][c] = M[r][c+k] and rot_R^s(M)[r][c] = M[r+s][c], indices modulo d.  Only S is kept
+ * in memory; this call makes the rearranged plaintexts number k = i + j b for k_first <= k < k_first +
+ * k_count from it:
+ *
+ *     out_dev[e][k - k_first][r][c] = S_dev[e][(r - l k - (k / b) b) mod d][(c + k) mod d] .
+ *
+ *   S_dev     device, [batch][d][d] uint64 words (any content: the words are moved, not interpreted)
+ *   out_dev   device, [batch][k_count][d][d] uint64; written completely; must not overlap S_dev
+ *   batch     number of stored matrices (heads x limbs x ...), >= 1
+ *   d         matrix dimension, 1 <= d <= 32768 (the paper's head dimension is 128)
+ *   ell       the power l of tau the output of the PCMM is to carry (any sign), |l| <= 2^31
+ *   b         baby steps per giant step; must divide d
+ *   k_first, k_count   the run of plaintexts to make, 0 <= k_first, k_first + k_count <= d
+ *   device, stream     HIP device ordinal and hipStream_t (NULL = default stream); asynchronous
+ *
+ * No scratch memory, no plan.  The sigma and tau maps that produce S, and everything homomorphic
+ * (rotations of ciphertexts, key switching), are not part of this library.  PCMM_EINVAL for null or
+ * aliased pointers, sizes out of range and b not dividing d; PCMM_EUNSUPPORTED beyond 2^40 stored words
+ * or 2^31 - 1 tiles of 4096 words.
+ */
+pcmm_status pcmm_slot_rearrange(const uint64_t *S_dev, uint64_t *out_dev, int64_t batch, int64_t d, int64_t ell,
+                                int64_t b, int64_t k_first, int64_t k_count, int32_t device, void *stream);
+
+/*
  * Frees everything the plan owns (the converted weights of Section 5.3, the digit scratch, the
  * constants).  The caller makes sure no run of the plan is still in flight.  NULL is ignored.
  */

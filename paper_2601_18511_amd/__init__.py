@@ -15,6 +15,7 @@ from .pcmm import (  # noqa: F401
     pcmm_ring_compose,
     pcmm_ring_decompose,
     pcmm_run,
+    pcmm_slot_rearrange,
     pcmm_run_noalloc,
     pcmm_run_profiled,
     pcmm_status_str,

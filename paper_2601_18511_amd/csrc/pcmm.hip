@@ -28,6 +28,7 @@
 #include "pcmm_host.hpp"
 #include "pcmm_device.hpp"
 #include "pcmm_shortk.hpp"
+#include "pcmm_hip_util.hpp"
 
 using namespace pcmm_device;
 
@@ -591,23 +592,8 @@ struct pcmm_plan {
 
 namespace {
 
-struct DevGuard {
-    int prev;
-    bool ok;
-    explicit DevGuard(int dev) : prev(-1), ok(false)
-    {
-        if (hipGetDevice(&prev) != hipSuccess) return;
-        if (prev != dev && hipSetDevice(dev) != hipSuccess) return;
-        ok = true;
-    }
-    ~DevGuard()
-    {
-        int cur = -1;
-        if (prev >= 0 && hipGetDevice(&cur) == hipSuccess && cur != prev) (void)hipSetDevice(prev);
-    }
-};
-
 using pcmm_host::tile_mt;
+using pcmm_hip_util::DevGuard;
 
 constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mutex;

@@ -26,6 +26,7 @@ EXPORTED = (
     "pcmm_mfma_probe",
     "pcmm_ring_decompose",
     "pcmm_ring_compose",
+    "pcmm_slot_rearrange",
 )
 
 _lib: Optional[ctypes.CDLL] = None
@@ -63,6 +64,8 @@ def load_library() -> ctypes.CDLL:
     for fn in (lib.pcmm_ring_decompose, lib.pcmm_ring_compose):
         fn.argtypes = [vp, vp, i64, i64, i64, i32, vp]
         fn.restype = ctypes.c_int
+    lib.pcmm_slot_rearrange.argtypes = [vp, vp, i64, i64, i64, i64, i64, i64, i32, vp]
+    lib.pcmm_slot_rearrange.restype = ctypes.c_int
     lib.pcmm_plan_destroy.argtypes = [vp]
     lib.pcmm_plan_destroy.restype = None
     lib.pcmm_status_str.argtypes = [ctypes.c_int]
@@ -200,6 +203,26 @@ def pcmm_ring_decompose(p: torch.Tensor, parts: torch.Tensor, N: int, k: int, st
 def pcmm_ring_compose(parts: torch.Tensor, p: torch.Tensor, N: int, k: int, stream=None) -> None:
     """p[..., i*k + j] = parts[..., j, i]: the inverse of pcmm_ring_decompose. Asynchronous."""
     _ring_call("pcmm_ring_compose", parts, p, N, k, stream)
+
+
+def pcmm_slot_rearrange(S: torch.Tensor, out: torch.Tensor, d: int, ell: int, b: int, k_first: int = 0,
+                        k_count: Optional[int] = None, stream=None) -> None:
+    """out[e][k - k_first][r][c] = S[e][(r - ell k - (k // b) b) mod d][(c + k) mod d]: the rearranged plaintexts
+    number k_first .. k_first + k_count - 1 of the slot-encoded PCMM, from the stored S = tau^ell o sigma(pt_A).
+    S is [..][d][d], out is [..][k_count][d][d]. Asynchronous."""
+    if k_count is None:
+        k_count = int(d) - int(k_first)
+    for t in (S, out):
+        if not t.is_cuda or not t.is_contiguous() or t.dtype not in (torch.int64, torch.uint64):
+            raise ValueError("the rearrangement moves contiguous 64-bit integer tensors on the GPU")
+    d = int(d)
+    if d <= 0 or S.numel() % (d * d) or S.device != out.device or out.numel() != S.numel() * int(k_count):
+        raise ValueError("S must hold whole d x d matrices and out k_count times as many words")
+    with torch.cuda.device(S.device):
+        rc = load_library().pcmm_slot_rearrange(S.data_ptr(), out.data_ptr(), S.numel() // (d * d), d, int(ell), int(b),
+                                                int(k_first), int(k_count), S.device.index, _stream_handle(stream))
+    if rc != PCMM_OK:
+        raise PcmmError(rc, "pcmm_slot_rearrange")
 
 
 def pcmm_plan_destroy(plan: PcmmPlan) -> None:

@@ -82,6 +82,22 @@ def test_argument_validation_needs_no_device():
         assert fn(dummy, other, 1 << 36, 1 << 16, 8, 0, None) == binding.PCMM_EUNSUPPORTED
 
 
+def test_slot_rearrange_argument_validation_needs_no_device():
+    lib = pkg.load_library()
+    a, b = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x2000)     # never dereferenced: validation fails first
+    f = lib.pcmm_slot_rearrange
+    assert f(None, b, 1, 8, 1, 2, 0, 8, 0, None) == binding.PCMM_EINVAL
+    assert f(a, a, 1, 8, 1, 2, 0, 8, 0, None) == binding.PCMM_EINVAL          # aliased
+    assert f(a, b, 0, 8, 1, 2, 0, 8, 0, None) == binding.PCMM_EINVAL
+    assert f(a, b, 1, 0, 1, 2, 0, 8, 0, None) == binding.PCMM_EINVAL
+    assert f(a, b, 1, 8, 1, 3, 0, 8, 0, None) == binding.PCMM_EINVAL          # b does not divide d
+    assert f(a, b, 1, 8, 1, 2, 0, 9, 0, None) == binding.PCMM_EINVAL          # run of plaintexts past d
+    assert f(a, b, 1, 8, 1, 2, -1, 2, 0, None) == binding.PCMM_EINVAL
+    assert f(a, b, 1, 8, 1, 2, 0, 8, -1, None) == binding.PCMM_EINVAL
+    assert f(a, b, 1, 40000, 1, 2, 0, 8, 0, None) == binding.PCMM_EUNSUPPORTED
+    assert f(a, b, 1 << 30, 4096, 1, 2, 0, 8, 0, None) == binding.PCMM_EUNSUPPORTED
+
+
 def test_header_is_plain_c(tmp_path):
     """include/pcmm.h compiles as C99 and as C++ and declares what the binding expects."""
     import shutil
