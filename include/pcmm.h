@@ -199,6 +199,62 @@ pcmm_status pcmm_slot_rearrange(const uint64_t *S_dev, uint64_t *out_dev, int64_
                                 int64_t b, int64_t k_first, int64_t k_count, int32_t device, void *stream);
 
 /*
+ * PCMv: the ring products of the decode-time plaintext-ciphertext matrix-vector multiplication.  In the decoding
+ * stage the matrix-matrix products of the linear layers become matrix-vector products (Section 3.2, last paragraph),
+ * evaluated at ring degree 4096 in coefficient encoding (Table "he-operators", row PCMv) with the converted weights
+ * kept as plaintext polynomials in the NTT domain (Section 5.3, Table "model-conversion-memory").  A plaintext
+ * polynomial multiplies both components of a ciphertext (Appendix A).  For plaintext polynomials pt[m][k] and
+ * ciphertexts ct[k] = (a_k, b_k), for every RNS limb j, this part of the library computes
+ *
+ *     out_j[m][c] = sum_{k<Kp} pt[m][k] * ct_j[k][c]    in  Z_{q_j}[X] / (X^N + 1),    c in {a, b},
+ *
+ * coefficients in [0, q_j), exactly.  Which weights go into which plaintext polynomial, and the extraction and
+ * repacking of the useful coefficients of the products, belong to the algorithm the paper adopts by reference
+ * for PCMv and are not part of this library.
+ */
+typedef struct pcmv_plan pcmv_plan; /* opaque; owns the NTT-domain plaintexts, the twiddle tables and the NTT scratch */
+
+/*
+ * Build a PCMv plan: transforms the plaintext polynomials into the NTT domain, once (the model conversion of
+ * Section 5.3 for the PCMv weights).
+ *
+ *   out          receives the plan (NULL on failure)
+ *   Mp, Kp       pt is Mp x Kp polynomials: Mp output polynomials, Kp input ciphertexts; Kp <= 4096, Mp <= 2^24
+ *   N            ring degree, a power of two, 2 <= N <= 4096 (the paper uses 4096 for PCMv)
+ *   L            number of RNS limbs, 1 <= L <= 64
+ *   primes_host  [L] host array; each q_j prime, q_j = 1 (mod 2N), 2^(prime_bits-1) < q_j < 2^prime_bits
+ *   prime_bits   24 <= prime_bits <= 50 (the transforms compute in exact double-precision arithmetic)
+ *   pt_dev       device, [Mp][Kp][N] int32_t: the plaintext polynomials' signed coefficients (coefficient domain),
+ *                the same for every limb; read during this call only
+ *   device, stream   HIP device ordinal and hipStream_t (NULL = default); the call synchronises the stream
+ *
+ * PCMM_EINVAL for null pointers, sizes out of range, N not a power of two, an even or wrong-size prime, a modulus
+ * that is not 1 mod 2N or for which no primitive 2N-th root of unity is found (primality itself is the caller's
+ * precondition); PCMM_EUNSUPPORTED for primes above 50 bits,
+ * N above 4096, Kp above 4096 or more than 2^31 - 256 polynomials per limb set.
+ */
+pcmm_status pcmv_plan_create(pcmv_plan **out, int64_t Mp, int64_t Kp, int64_t N, int32_t L, const uint64_t *primes_host,
+                             int32_t prime_bits, const int32_t *pt_dev, int32_t device, void *stream);
+
+/* Device bytes the PCMv plan owns (8 Mp Kp N L for the NTT-domain plaintexts, plus tables and scratch). 0 for NULL. */
+size_t pcmv_plan_workspace_bytes(const pcmv_plan *plan);
+
+/*
+ * One PCMv: out_j[m][c] = sum_k pt[m][k] * ct_j[k][c] in Z_{q_j}[X]/(X^N+1) (Sections 3.2 and 5.3, as above).
+ *
+ *   ct_dev   device, [L][Kp][2][N] uint64: limb j of ciphertext k, component a (index 0) then b (index 1), coefficient
+ *            domain, residues in [0, q_j) - a caller precondition, not checked; read only
+ *   out_dev  device, [L][Mp][2][N] uint64, coefficient domain; every entry written; must not overlap ct_dev
+ *   stream   hipStream_t (NULL = default stream); asynchronous
+ *
+ * Two runs of the same plan must not overlap in time (they share the plan's NTT scratch).
+ */
+pcmm_status pcmv_run(const pcmv_plan *plan, const uint64_t *ct_dev, uint64_t *out_dev, void *stream);
+
+/* Frees everything a PCMv plan owns.  NULL is ignored.  No run of the plan may still be in flight. */
+void pcmv_plan_destroy(pcmv_plan *plan);
+
+/*
  * Frees everything the plan owns (the converted weights of Section 5.3, the digit scratch, the
  * constants).  The caller makes sure no run of the plan is still in flight.  NULL is ignored.
  */

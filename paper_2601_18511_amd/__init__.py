@@ -19,4 +19,9 @@ from .pcmm import (  # noqa: F401
     pcmm_run_noalloc,
     pcmm_run_profiled,
     pcmm_status_str,
+    PcmvPlan,
+    pcmv_plan_create,
+    pcmv_plan_destroy,
+    pcmv_plan_workspace_bytes,
+    pcmv_run,
 )

@@ -9,10 +9,10 @@ import tempfile
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 # translation units of the library (each holds its own kernels; no device code crosses files)
-SOURCES = [os.path.join(CSRC, n) for n in ("pcmm.hip", "pcmm_shortk.hip", "pcmm_slot.hip")]
+SOURCES = [os.path.join(CSRC, n) for n in ("pcmm.hip", "pcmm_shortk.hip", "pcmm_slot.hip", "pcmv.hip")]
 SRC = SOURCES[0]
 HEADER = os.path.join(os.path.dirname(_HERE), "include", "pcmm.h")
-INTERNAL_HEADERS = [os.path.join(CSRC, n) for n in ("pcmm_host.hpp", "pcmm_device.hpp", "pcmm_shortk.hpp", "pcmm_hip_util.hpp")]
+INTERNAL_HEADERS = [os.path.join(CSRC, n) for n in ("pcmm_host.hpp", "pcmm_device.hpp", "pcmm_shortk.hpp", "pcmm_hip_util.hpp", "pcmv_host.hpp")]
 LIB = os.path.join(_HERE, "libpcmm.so")
 STAMP = LIB + ".stamp"          # digest of the sources and flags the library was built from
 

@@ -27,6 +27,10 @@ EXPORTED = (
     "pcmm_ring_decompose",
     "pcmm_ring_compose",
     "pcmm_slot_rearrange",
+    "pcmv_plan_create",
+    "pcmv_plan_workspace_bytes",
+    "pcmv_run",
+    "pcmv_plan_destroy",
 )
 
 _lib: Optional[ctypes.CDLL] = None
@@ -66,6 +70,14 @@ def load_library() -> ctypes.CDLL:
         fn.restype = ctypes.c_int
     lib.pcmm_slot_rearrange.argtypes = [vp, vp, i64, i64, i64, i64, i64, i64, i32, vp]
     lib.pcmm_slot_rearrange.restype = ctypes.c_int
+    lib.pcmv_plan_create.argtypes = [ctypes.POINTER(vp), i64, i64, i64, i32, vp, i32, vp, i32, vp]
+    lib.pcmv_plan_create.restype = ctypes.c_int
+    lib.pcmv_plan_workspace_bytes.argtypes = [vp]
+    lib.pcmv_plan_workspace_bytes.restype = ctypes.c_size_t
+    lib.pcmv_run.argtypes = [vp, vp, vp, vp]
+    lib.pcmv_run.restype = ctypes.c_int
+    lib.pcmv_plan_destroy.argtypes = [vp]
+    lib.pcmv_plan_destroy.restype = None
     lib.pcmm_plan_destroy.argtypes = [vp]
     lib.pcmm_plan_destroy.restype = None
     lib.pcmm_status_str.argtypes = [ctypes.c_int]
@@ -223,6 +235,64 @@ def pcmm_slot_rearrange(S: torch.Tensor, out: torch.Tensor, d: int, ell: int, b:
                                                 int(k_first), int(k_count), S.device.index, _stream_handle(stream))
     if rc != PCMM_OK:
         raise PcmmError(rc, "pcmm_slot_rearrange")
+
+
+class PcmvPlan:
+    """Owner of one pcmv_plan handle."""
+
+    def __init__(self, handle: int, Mp: int, Kp: int, N: int, L: int, device: int):
+        self.handle = handle
+        self.Mp, self.Kp, self.N, self.L, self.device = Mp, Kp, N, L, device
+
+    def destroy(self) -> None:
+        if self.handle:
+            load_library().pcmv_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def pcmv_plan_create(pt: torch.Tensor, primes: Sequence[int], prime_bits: int, stream=None) -> PcmvPlan:
+    """PCMv plan for the device tensor pt ([Mp][Kp][N] int32 plaintext coefficients) and the host list of primes."""
+    if not pt.is_cuda or pt.dim() != 3 or pt.dtype != torch.int32 or not pt.is_contiguous():
+        raise ValueError("pt must be a contiguous [Mp][Kp][N] int32 tensor on the GPU")
+    Mp, Kp, N = pt.shape
+    L = len(primes)
+    arr = (ctypes.c_uint64 * max(L, 1))(*[int(q) for q in primes])
+    out = ctypes.c_void_p()
+    with torch.cuda.device(pt.device):
+        rc = load_library().pcmv_plan_create(ctypes.byref(out), Mp, Kp, N, L, ctypes.cast(arr, ctypes.c_void_p),
+                                             int(prime_bits), pt.data_ptr(), pt.device.index, _stream_handle(stream))
+    if rc != PCMM_OK:
+        raise PcmmError(rc, "pcmv_plan_create")
+    return PcmvPlan(out.value, Mp, Kp, N, L, pt.device.index)
+
+
+def pcmv_plan_workspace_bytes(plan: PcmvPlan) -> int:
+    return int(load_library().pcmv_plan_workspace_bytes(plan.handle))
+
+
+def pcmv_run(plan: PcmvPlan, ct: torch.Tensor, out: torch.Tensor, stream=None) -> None:
+    """Enqueue out[j][m][c] = sum_k pt[m][k] * ct[j][k][c] in Z_{q_j}[X]/(X^N+1). ct is [L][Kp][2][N], out [L][Mp][2][N]."""
+    if plan.handle is None:
+        raise ValueError("plan was destroyed")
+    for name, t, rows in (("ct", ct, plan.Kp), ("out", out, plan.Mp)):
+        if not t.is_cuda or t.device.index != plan.device or not t.is_contiguous():
+            raise ValueError("%s must be a contiguous tensor on the plan's device" % name)
+        if t.dtype not in (torch.int64, torch.uint64) or tuple(t.shape) != (plan.L, rows, 2, plan.N):
+            raise ValueError("%s must be 64-bit integers of shape [L][%d][2][N]" % (name, rows))
+    with torch.cuda.device(plan.device):
+        rc = load_library().pcmv_run(plan.handle, ct.data_ptr(), out.data_ptr(), _stream_handle(stream))
+    if rc != PCMM_OK:
+        raise PcmmError(rc, "pcmv_run")
+
+
+def pcmv_plan_destroy(plan: PcmvPlan) -> None:
+    plan.destroy()
 
 
 def pcmm_plan_destroy(plan: PcmmPlan) -> None:

@@ -16,7 +16,7 @@ HEADER = os.path.join(ROOT, "include", "pcmm.h")
 def _declared_functions():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(pcmm_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(pcm[mv]_[a-z_]+)\s*\(", text)))
 
 
 def test_header_symbols_are_exported_and_bound():

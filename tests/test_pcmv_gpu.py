@@ -1,0 +1,140 @@
+"""Parity of the PCMv HIP path (forward NTT, pointwise multiply-accumulate, inverse NTT) against the schoolbook
+oracle, coefficient by coefficient, through the C ABI (GPU).  Integer work: the bar is bit-exact."""
+import numpy as np
+import pytest
+
+import pcmm_inputs as pi
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_gpu(pt, ct, primes, bits, dev):
+    import torch
+
+    import paper_2601_18511_amd as pkg
+
+    plan = pkg.pcmv_plan_create(torch.from_numpy(pt.astype(np.int32)).to(dev), primes, bits)
+    ct_dev = torch.from_numpy(ct.view(np.int64)).to(dev)
+    out = torch.full((ct.shape[0], pt.shape[0], 2, pt.shape[2]), -1, dtype=torch.int64, device=dev)
+    pkg.pcmv_run(plan, ct_dev, out)
+    torch.cuda.synchronize()
+    assert pkg.pcmv_plan_workspace_bytes(plan) >= 8 * pt.size * ct.shape[0]
+    pkg.pcmv_plan_destroy(plan)
+    return out.cpu().numpy().view(np.uint64)
+
+
+def _case(rng, Mp, Kp, N, primes, wmax):
+    pt = rng.integers(-wmax, wmax, size=(Mp, Kp, N), dtype=np.int64)
+    ct = np.stack([rng.integers(0, q, size=(Kp, 2, N), dtype=np.uint64) for q in primes])
+    return pt, ct
+
+
+@pytest.mark.parametrize("Mp,Kp,N,bits,L,wmax", [
+    (1, 1, 2, 36, 1, 1 << 15), (3, 1, 4, 36, 2, 1 << 15), (2, 2, 8, 36, 2, 1 << 15), (5, 3, 16, 50, 2, 1 << 15),
+    (2, 1, 64, 24, 2, 1 << 7), (3, 2, 128, 30, 2, 1 << 15), (2, 1, 256, 36, 3, 1 << 15), (4, 4, 512, 50, 2, 1 << 15),
+    (2, 3, 1024, 44, 2, 1 << 20), (3, 1, 2048, 50, 1, 1 << 30), (2, 2, 4096, 36, 2, 1 << 15), (3, 1, 4096, 50, 2, 1 << 15),
+    (1, 16, 256, 50, 1, 1 << 15),
+])
+def test_random_shapes_bit_exact(gpu_device, Mp, Kp, N, bits, L, wmax):
+    from oracle import pcmv_oracle
+
+    rng = np.random.default_rng(Mp * 1000 + Kp * 100 + N)
+    primes = pi.ntt_primes(bits, 2 * N, L)
+    pt, ct = _case(rng, Mp, Kp, N, primes, wmax)
+    got = _run_gpu(pt, ct, primes, bits, gpu_device)
+    want = pcmv_oracle(pt, ct, primes)
+    assert (got == want).all(), int((got != want).sum())
+
+
+@pytest.mark.parametrize("bits,N", [(50, 256), (36, 1024), (24, 64), (50, 4096)])
+def test_extreme_values(gpu_device, bits, N):
+    """Plaintext coefficients at +-max, residues at 0, 1, q-1, q/2: the largest products and sums the exact
+    double-precision arithmetic has to carry."""
+    from oracle import pcmv_oracle
+
+    rng = np.random.default_rng(bits + N)
+    primes = pi.ntt_primes(bits, 2 * N, 2)
+    Mp, Kp = 4, 3
+    wmax = (1 << 31) - 1
+    pt = rng.integers(-wmax, wmax, size=(Mp, Kp, N), dtype=np.int64)
+    pt[0] = wmax
+    pt[1] = -wmax
+    pt[2, :, ::2] = 0
+    ct = np.empty((2, Kp, 2, N), dtype=np.uint64)
+    for j, q in enumerate(primes):
+        pats = np.array([0, 1, q - 1, q // 2, q // 2 + 1, q - 2], dtype=np.uint64)
+        ct[j] = pats[rng.integers(0, len(pats), size=(Kp, 2, N))]
+        ct[j, 0, 0, :] = q - 1
+        ct[j, 0, 1, :] = 0
+    got = _run_gpu(pt, ct, primes, bits, gpu_device)
+    want = pcmv_oracle(pt, ct, primes)
+    assert (got == want).all(), int((got != want).sum())
+
+
+def test_monomial_plaintexts_shift_the_ciphertext(gpu_device):
+    rng = np.random.default_rng(5)
+    N = 512
+    primes = pi.ntt_primes(36, 2 * N, 2)
+    shifts = [0, 1, 100, N - 1]
+    pt = np.zeros((len(shifts), 1, N), dtype=np.int64)
+    for r, s in enumerate(shifts):
+        pt[r, 0, s] = 1
+    ct = np.stack([rng.integers(0, q, size=(1, 2, N), dtype=np.uint64) for q in primes])
+    got = _run_gpu(pt, ct, primes, 36, gpu_device)
+    for j, q in enumerate(primes):
+        for r, s in enumerate(shifts):
+            for c in range(2):
+                x = ct[j, 0, c]
+                want = np.concatenate([(np.uint64(q) - x[N - s:]) % np.uint64(q), x[:N - s]]) if s else x
+                assert (got[j, r, c] == want).all()
+
+
+def test_decode_projection_shape_sampled_rows(gpu_device):
+    """The benchmarked decode shape (4096 plaintext polynomials of degree 4096, one input ciphertext, two 36-bit limbs):
+    seeded rows against the oracle, every output in range, and plan reuse with a second ciphertext."""
+    import torch
+
+    import paper_2601_18511_amd as pkg
+    from oracle import pcmv_oracle_rows
+
+    Mp, Kp, N, bits, L = 4096, 1, 4096, 36, 2
+    primes = pi.ntt_primes(bits, 2 * N, L)
+    g = torch.Generator(device=gpu_device)
+    g.manual_seed(21)
+    pt = torch.randint(-(1 << 15), 1 << 15, (Mp, Kp, N), dtype=torch.int32, device=gpu_device, generator=g)
+    plan = pkg.pcmv_plan_create(pt, primes, bits)
+    out = torch.empty((L, Mp, 2, N), dtype=torch.int64, device=gpu_device)
+    rows = [0, 1, 777, 2048, Mp - 1]
+    for trial in range(2):
+        ct = torch.stack([torch.randint(0, q, (Kp, 2, N), dtype=torch.int64, device=gpu_device, generator=g) for q in primes])
+        pkg.pcmv_run(plan, ct, out)
+        torch.cuda.synchronize()
+        for j, q in enumerate(primes):
+            assert bool(((out[j] >= 0) & (out[j] < q)).all())
+        want = pcmv_oracle_rows(pt[rows].cpu().numpy(), ct.cpu().numpy().view(np.uint64), primes, list(range(len(rows))))
+        assert (out[:, rows].cpu().numpy().view(np.uint64) == want).all()
+    pkg.pcmv_plan_destroy(plan)
+
+
+def test_bad_arguments_are_status_codes(gpu_device):
+    import torch
+
+    import paper_2601_18511_amd as pkg
+
+    N = 64
+    pt = torch.zeros((2, 1, N), dtype=torch.int32, device=gpu_device)
+    good = pi.ntt_primes(36, 2 * N, 1)
+    for primes, bits, status in (([good[0] - 2 * N + 2], 36, pkg.pcmm.PCMM_EINVAL),                  # even
+                                 ([pi.ntt_primes(36, 2, 1)[0]], 36, None),                           # maybe not 1 mod 2N
+                                 (pi.ntt_primes(56, 2 * N, 1), 56, pkg.pcmm.PCMM_EUNSUPPORTED),
+                                 (good, 35, pkg.pcmm.PCMM_EINVAL)):
+        q = primes[0]
+        if status is None:
+            if (q - 1) % (2 * N) == 0:
+                continue
+            status = pkg.pcmm.PCMM_EINVAL
+        with pytest.raises(pkg.PcmmError) as e:
+            pkg.pcmv_plan_create(pt, primes, bits)
+        assert e.value.status == status
+    with pytest.raises(ValueError):
+        pkg.pcmv_plan_create(pt.to(torch.int64), good, 36)
