@@ -151,6 +151,50 @@ def slot_rearrange_rates(pkg, torch, dev, copy_GBs: float, iters: int = 10):
             "sample_matches_index_formula": bool(torch.equal(out[:, k], want))}
 
 
+def pcmv_rates(pkg, pi, torch, dev, copy_GBs: float, iters: int = 10, check: bool = True):
+    """The decode-time ring products (PCMv; not part of the timed step): degree-4096 plaintext polynomials in the NTT
+    domain times one or four input ciphertexts, two 36-bit limbs.  'o_proj': 4096 plaintext polynomials x 1 ciphertext
+    (a 4096 x 4096 matrix, one polynomial per row); 'down_proj': 4096 x 4 (a 4096 x 14336 matrix, rows cut into four
+    polynomials).  HBM-bound: the NTT-domain plaintexts are read once, the products written once."""
+    import numpy as np
+
+    N, bits, L = 4096, 36, 2
+    primes = pi.ntt_primes(bits, 2 * N, L)
+    out = {"ring_degree": N, "primes": "%d x %d bits" % (L, bits), "dtype": "f64 (exact integer arithmetic in doubles)"}
+    g = torch.Generator(device=dev)
+    g.manual_seed(31)
+    for name, Mp, Kp in (("o_proj", 4096, 1), ("down_proj", 4096, 4)):
+        pt = torch.randint(-(1 << 15), 1 << 15, (Mp, Kp, N), dtype=torch.int32, device=dev, generator=g)
+        plan = pkg.pcmv_plan_create(pt, primes, bits)
+        ct = torch.stack([torch.randint(0, q, (Kp, 2, N), dtype=torch.int64, device=dev, generator=g) for q in primes])
+        res = torch.empty((L, Mp, 2, N), dtype=torch.int64, device=dev)
+        stream = torch.cuda.current_stream()
+        pkg.pcmv_run(plan, ct, res, stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(iters):
+            pkg.pcmv_run(plan, ct, res, stream)
+        e1.record(stream)
+        e1.synchronize()
+        ms = e0.elapsed_time(e1) / iters
+        nbytes = 8.0 * L * N * (Mp * Kp + 2 * Mp + 2 * Kp)          # plaintexts read, products written, ciphertexts read
+        rec = {"plaintext_polynomials": Mp * Kp, "input_ciphertexts": Kp, "ms": ms, "algorithmic_bytes": nbytes,
+               "GBs": nbytes / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+               "frac_of_copy": nbytes / (ms * 1e-3) / 1e9 / copy_GBs,
+               "ring_multiply_accumulates_per_s": 2.0 * L * Mp * Kp / (ms * 1e-3),
+               "workspace_bytes": pkg.pcmv_plan_workspace_bytes(plan)}
+        if check:
+            from oracle import pcmv_oracle_rows
+
+            rows = [0, 1234, Mp - 1]
+            want = pcmv_oracle_rows(pt[rows].cpu().numpy(), ct.cpu().numpy().view(np.uint64), primes, list(range(len(rows))))
+            rec["gpu_rows_match_oracle"] = bool((res[:, rows].cpu().numpy().view(np.uint64) == want).all())
+        out[name] = rec
+        pkg.pcmv_plan_destroy(plan)
+        del pt, ct, res
+    return out
+
+
 def library_int8_gemm(torch, dev, wl, iters: int = 5):
     """Context only: the vendor library's plain int8 GEMM (torch._int_mm) on the raw int8 products of the same
     workload, W[M][K] x digit planes [K][Ncols*L*D] -> int32, random int8 data.  No digit split, no recombination,
@@ -271,8 +315,8 @@ def main() -> int:
     ap.add_argument("--only", action="store_true", help="measure the headline workload only, not the others")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip every oracle run (no row check either)")
     ap.add_argument("--no-ring-switch", action="store_true",
-                    help="skip the (untimed-step) measurements of the permutation kernels beside the PCMM: ring switching "
-                         "and the slot-encoded PCMM's plaintext rearrangement")
+                    help="skip the (untimed-step) measurements of the kernels beside the PCMM: ring switching, the "
+                         "slot-encoded PCMM's plaintext rearrangement and the decode-time PCMv")
     ap.add_argument("--no-library-gemm", action="store_true",
                     help="skip timing the vendor library's plain int8 GEMM on the same int8 work (context only)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -369,11 +413,13 @@ def main() -> int:
     if not args.no_ring_switch:
         result["ring_switch"] = ring_switch_rates(pkg, torch, dev, copy_GBs)
         result["slot_rearrange"] = slot_rearrange_rates(pkg, torch, dev, copy_GBs)
+        result["pcmv"] = pcmv_rates(pkg, pi, torch, dev, copy_GBs, check=not args.no_cpu_baseline)
+        ok = ok and all(v.get("gpu_rows_match_oracle", True) for v in result["pcmv"].values() if isinstance(v, dict))
     if not args.no_library_gemm:
         result["library_int8_gemm"] = library_int8_gemm(torch, dev, head)
     print(json.dumps(result))
     if not ok:
-        bad = [r["name"] for r in records if not r.get("gpu_rows_match_oracle", True)]
+        bad = [r["name"] for r in records if not r.get("gpu_rows_match_oracle", True)] or ["pcmv"]
         print("bench.py: GPU rows differ from the oracle for: %s -- the figures above are NOT a valid measurement"
               % ", ".join(bad), file=sys.stderr)
         return 1
