@@ -98,6 +98,39 @@ def test_slot_rearrange_argument_validation_needs_no_device():
     assert f(a, b, 1 << 30, 4096, 1, 2, 0, 8, 0, None) == binding.PCMM_EUNSUPPORTED
 
 
+def test_pcmv_argument_validation_needs_no_device():
+    lib = pkg.load_library()
+    out = ctypes.c_void_p(123)
+    dummy = ctypes.c_void_p(0x1000)     # never dereferenced: validation fails first
+    N = 64
+    q = (ctypes.c_uint64 * 1)(68719475713)          # 2^36 - 2^10 + 1... any odd 36-bit number = 1 mod 128 will do for these checks
+    q[0] = ((1 << 36) - 1) // 128 * 128 + 1
+    qp = ctypes.cast(q, ctypes.c_void_p)
+
+    def create(Mp=2, Kp=1, n=N, L=1, primes=qp, bits=36, pt=dummy, dev=0):
+        return lib.pcmv_plan_create(ctypes.byref(out), Mp, Kp, n, L, primes, bits, pt, dev, None)
+
+    assert create(Mp=0) == binding.PCMM_EINVAL and out.value is None
+    assert create(Kp=0) == binding.PCMM_EINVAL
+    assert create(n=1) == binding.PCMM_EINVAL
+    assert create(n=96) == binding.PCMM_EINVAL                 # not a power of two
+    assert create(L=0) == binding.PCMM_EINVAL
+    assert create(L=65) == binding.PCMM_EINVAL
+    assert create(primes=None) == binding.PCMM_EINVAL
+    assert create(pt=None) == binding.PCMM_EINVAL
+    assert create(bits=35) == binding.PCMM_EINVAL              # prime not of that size
+    assert create(dev=-1) == binding.PCMM_EINVAL
+    assert create(n=1 << 20) == binding.PCMM_EINVAL            # q is not 1 mod 2N
+    assert create(n=8192) in (binding.PCMM_EINVAL, binding.PCMM_EUNSUPPORTED)
+    assert create(Kp=5000) == binding.PCMM_EUNSUPPORTED
+    big = (ctypes.c_uint64 * 1)(((1 << 56) - 1) // 128 * 128 + 1)
+    assert create(primes=ctypes.cast(big, ctypes.c_void_p), bits=56) == binding.PCMM_EUNSUPPORTED
+    assert lib.pcmv_plan_create(None, 2, 1, N, 1, qp, 36, dummy, 0, None) == binding.PCMM_EINVAL
+    assert lib.pcmv_run(None, dummy, dummy, None) == binding.PCMM_EINVAL
+    assert lib.pcmv_plan_workspace_bytes(None) == 0
+    lib.pcmv_plan_destroy(None)
+
+
 def test_header_is_plain_c(tmp_path):
     """include/pcmm.h compiles as C99 and as C++ and declares what the binding expects."""
     import shutil

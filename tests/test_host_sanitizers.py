@@ -2,7 +2,8 @@
 
 Two things run sanitized here:
   * the library's host-side planning (argument validation, digit count, tile geometry, buffer sizes,
-    k-step offsets, per-limb constants) -- csrc/pcmm_host.hpp compiled into tests/host/plan_geometry_check.cpp;
+    k-step offsets, per-limb constants) -- csrc/pcmm_host.hpp compiled into tests/host/plan_geometry_check.cpp,
+    and the PCMv planning (roots of unity, twiddle tables) -- csrc/pcmv_host.hpp in tests/host/pcmv_tables_check.cpp;
   * the C oracles: pcmm_oracle.c and pcmv_oracle.c are built a second time with the sanitizers and their pins run
     on those builds in a child interpreter (the sanitizer runtime has to be loaded before python starts).
 """
@@ -28,6 +29,17 @@ def test_plan_geometry_under_sanitizers(tmp_path):
     subprocess.run(["g++", "-std=c++17", "-Wall", "-Wextra", "-Werror"] + SAN +
                    ["-I", os.path.join(ROOT, "paper_2601_18511_amd", "csrc"), "-o", str(exe),
                     os.path.join(ROOT, "tests", "host", "plan_geometry_check.cpp")], check=True)
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "all checks held" in r.stdout
+
+
+def test_pcmv_tables_under_sanitizers(tmp_path):
+    _need("g++")
+    exe = tmp_path / "pcmv_tables_check"
+    subprocess.run(["g++", "-std=c++17", "-Wall", "-Wextra", "-Werror"] + SAN +
+                   ["-I", os.path.join(ROOT, "paper_2601_18511_amd", "csrc"), "-o", str(exe),
+                    os.path.join(ROOT, "tests", "host", "pcmv_tables_check.cpp")], check=True)
     r = subprocess.run([str(exe)], capture_output=True, text=True)
     assert r.returncode == 0, r.stdout + r.stderr
     assert "all checks held" in r.stdout
