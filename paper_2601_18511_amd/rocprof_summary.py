@@ -39,7 +39,7 @@ HBM_PEAK_GBS = 8000.0
 N_SIMD = 1024            # 256 compute units x 4 SIMDs
 N_XCD = 8
 NOMINAL_GHZ = 2.4
-COPY_KERNEL = re.compile(r"elementwise|copyBuffer|copy_kernel", re.I)
+COPY_KERNEL = re.compile(r"copyBuffer|direct_copy_kernel")   # what a plain device-to-device copy runs as
 GIB = float(1 << 30)
 
 
@@ -97,6 +97,26 @@ def read_counters(directory: str) -> Tuple[Dict[str, Dict[str, List[float]]], Di
                 for k, cs in vals.items()}
     durations = {k: [v for _, v in sorted(d.items(), key=lambda kv: int(kv[0]))] for k, d in durs.items()}
     return counters, durations
+
+
+def read_grouped(directory: str, suffix: str):
+    """(kernel, Grid_Size) -> {"dur": [ns per dispatch], counter name: [value per dispatch]} from a kernel-trace or
+    counter-collection csv: the same kernel launched on different problem sizes stays apart."""
+    out: Dict[Tuple[str, int], Dict[str, Dict[str, float]]] = defaultdict(lambda: defaultdict(dict))
+    for path in find_csv(directory, suffix):
+        with open(path, newline="") as f:
+            for row in csv.DictReader(f):
+                if "Grid_Size" in row:          # counter collection: total work-items
+                    grid = int(float(row["Grid_Size"]))
+                else:                           # kernel trace: work-items per dimension
+                    grid = int(float(row["Grid_Size_X"])) * int(float(row["Grid_Size_Y"])) * int(float(row["Grid_Size_Z"]))
+                key = (short_name(row["Kernel_Name"]), grid)
+                disp = row["Dispatch_Id"]
+                out[key]["dur"][disp] = float(row["End_Timestamp"]) - float(row["Start_Timestamp"])
+                if "Counter_Name" in row:
+                    c = row["Counter_Name"]
+                    out[key][c][disp] = out[key][c].get(disp, 0.0) + float(row["Counter_Value"])
+    return {k: {c: list(d.values()) for c, d in v.items()} for k, v in out.items()}
 
 
 def merge_counters(dirs: Sequence[str]):
@@ -297,6 +317,38 @@ def counter_summary(workload: str, fig: dict, counters, durations, commands: Seq
     return "\n".join(lines) + "\n"
 
 
+STREAMING = re.compile(r"^(split_kernel|transpose_u64_kernel|slot_rearrange_kernel|ntt_kernel|mac_intt\w*|pack_w_kernel)")
+
+
+def streaming_summary(trace_dir: Optional[str], fetch_dir: str, write_dir: str, commands: Sequence[str],
+                      copy_kib: float, notes: Sequence[str]) -> str:
+    """The HBM-bound kernels beside the MFMA kernels: per (kernel, grid size) the launch time and the bytes the L2s
+    exchanged with the fabric (FETCH_SIZE + WRITE_SIZE, scaled by the calibration copy), hence the achieved GB/s."""
+    f = read_grouped(fetch_dir, "counter_collection.csv")
+    w = read_grouped(write_dir, "counter_collection.csv")
+    t = read_grouped(trace_dir, "kernel_trace.csv") if trace_dir else {}
+    flat_f = {k[0] + "@%d" % k[1]: {"FETCH_SIZE": v.get("FETCH_SIZE", [])} for k, v in f.items()}
+    flat_w = {k[0] + "@%d" % k[1]: {"WRITE_SIZE": v.get("WRITE_SIZE", [])} for k, v in w.items()}
+    cal_f, cal_w = copy_scale(flat_f, "FETCH_SIZE", copy_kib), copy_scale(flat_w, "WRITE_SIZE", copy_kib)
+    sf, sw = (cal_f[1] if cal_f else 1.0), (cal_w[1] if cal_w else 1.0)
+    lines = ["HBM-side traffic and achieved rates of the streaming kernels (rocprofv3), per launch, by kernel and grid size", "",
+             "commands (from /tmp with TMPDIR=/tmp, R = repository root):"] + ["  " + c for c in commands] + [""]
+    lines.append("calibration copy (1 GiB each way): FETCH_SIZE scale %.4f, WRITE_SIZE scale %.4f" % (sf, sw))
+    lines += list(notes) + ["", "%-34s %12s %6s %10s %10s %12s %12s %10s" %
+                            ("kernel", "grid", "calls", "avg_ms", "min_ms", "read GiB", "written GiB", "GB/s")]
+    for key in sorted(set(f) & set(w)):
+        if not STREAMING.search(key[0]):
+            continue
+        rd = mean(f[key]["FETCH_SIZE"]) * sf * 1024.0
+        wr = mean(w[key]["WRITE_SIZE"]) * sw * 1024.0
+        dur = t.get(key, f[key])["dur"]              # durations of the un-instrumented trace when there is one
+        lines.append("%-34s %12d %6d %10.4f %10.4f %12.3f %12.3f %10.0f" %
+                     (key[0], key[1], len(dur), mean(dur) / 1e6, min(dur) / 1e6, rd / GIB, wr / GIB,
+                      (rd + wr) / (mean(dur) * 1e-9) / 1e9))
+    lines.append("(GB/s = (read + written) / average duration; %.0f GB/s is the HBM peak)" % HBM_PEAK_GBS)
+    return "\n".join(lines) + "\n"
+
+
 # --------------------------------------------------------------------------------------------------
 def main(argv: Optional[Sequence[str]] = None) -> int:
     ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
@@ -306,6 +358,9 @@ def main(argv: Optional[Sequence[str]] = None) -> int:
     ap.add_argument("--command", action="append", default=[], help="a command line to quote in the summaries (repeatable)")
     ap.add_argument("--copy-kib", type=float, default=float(1 << 20), help="KiB the calibration copy reads (and writes)")
     ap.add_argument("--out-prefix", default="profiles/", help="prefix of the files written")
+    ap.add_argument("--streaming-out", help="also write the summary of the HBM-bound kernels beside the MFMA kernels "
+                                            "(needs --pmc directories of a FETCH_SIZE and a WRITE_SIZE run, in that order)")
+    ap.add_argument("--note", action="append", default=[], help="a line to add to the streaming summary (repeatable)")
     args = ap.parse_args(argv)
 
     fig = workload_figures(args.workload)
@@ -328,6 +383,12 @@ def main(argv: Optional[Sequence[str]] = None) -> int:
                                                 [c for c in pmc_cmds if "FETCH_SIZE" in c or "WRITE_SIZE" in c], args.copy_kib))
         put("_counters.txt", counter_summary(args.workload, fig, counters, durations,
                                              [c for c in pmc_cmds if "FETCH_SIZE" not in c and "WRITE_SIZE" not in c]))
+    if args.streaming_out:
+        if len(args.pmc) < 2:
+            ap.error("--streaming-out needs the FETCH_SIZE and the WRITE_SIZE run directories")
+        with open(args.streaming_out, "w") as f:
+            f.write(streaming_summary(args.trace, args.pmc[0], args.pmc[1], args.command, args.copy_kib, args.note))
+        written.append(args.streaming_out)
     for w in written:
         print(w)
     return 0 if written else 1

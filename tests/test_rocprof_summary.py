@@ -101,3 +101,14 @@ def test_command_line_writes_the_three_summaries(tmp_path):
     assert "rocprofv3 --pmc FETCH_SIZE" in open(os.path.join(out, names[1])).read()
     with pytest.raises(KeyError):
         rs.workload_figures("no_such_workload")
+
+
+def test_streaming_summary_groups_by_kernel_and_grid():
+    text = rs.streaming_summary(os.path.join(GOLD, "kt"), os.path.join(GOLD, "fetch"), os.path.join(GOLD, "write"),
+                                ["rocprofv3 ..."], float(1 << 20), ["a note"])
+    row = [x for x in text.splitlines() if x.startswith("split_kernel<7>")]
+    assert len(row) == 1
+    cols = row[0].split()
+    assert int(cols[1]) == 6291456 and int(cols[2]) == 12             # grid size; launches in the trace
+    assert abs(float(cols[5]) - 0.75) < 0.01 and abs(float(cols[6]) - 0.656) < 0.01   # A read, digit planes written (GiB)
+    assert 4500 < float(cols[7]) < 6500
