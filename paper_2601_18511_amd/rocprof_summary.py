@@ -150,16 +150,23 @@ def mean(xs: Sequence[float]) -> float:
 # --------------------------------------------------------------------------------------------------
 # derived figures
 # --------------------------------------------------------------------------------------------------
-def copy_scale(counters, counter: str, copy_kib: float) -> Optional[Tuple[float, float]]:
+def copy_scale(directories: Sequence[str], counter: str, copy_kib: float) -> Optional[Tuple[float, float]]:
     """(KiB the counter read for the calibration copy, scale = true KiB / counted KiB), or None without a copy.
-    The calibration copy is the largest dispatch of a copy kernel; copies within 20 % of it are averaged."""
-    vals = [v for k, cs in counters.items() if COPY_KERNEL.search(k) for v in cs.get(counter, [])]
-    if not vals or max(vals) <= 0:
+    bench.py --copy-calibration runs its plain device copy before anything else, so the calibration copy is the
+    FIRST dispatch of a copy kernel that moved a sizeable amount (input generators copy other sizes later)."""
+    best = None
+    for d in directories:
+        for path in find_csv(d, "counter_collection.csv"):
+            with open(path, newline="") as f:
+                for row in csv.DictReader(f):
+                    if row["Counter_Name"] != counter or not COPY_KERNEL.search(row["Kernel_Name"]):
+                        continue
+                    v, disp = float(row["Counter_Value"]), int(row["Dispatch_Id"])
+                    if v >= 0.25 * copy_kib and (best is None or disp < best[0]):
+                        best = (disp, v)
+    if best is None:
         return None
-    top = max(vals)
-    near = [v for v in vals if v >= 0.8 * top]
-    got = mean(near)
-    return got, copy_kib / got
+    return best[1], copy_kib / best[1]
 
 
 def workload_figures(name: str) -> dict:
@@ -215,12 +222,13 @@ def trace_summary(workload: str, fig: dict, trace: Dict[str, List[float]], comma
     return "\n".join(lines) + "\n"
 
 
-def traffic_summary(workload: str, fig: dict, counters, commands: Sequence[str], copy_kib: float) -> Optional[str]:
+def traffic_summary(workload: str, fig: dict, counters, commands: Sequence[str], copy_kib: float,
+                    directories: Sequence[str]) -> Optional[str]:
     g = pick(counters, r"^%s<" % fig["mfma_kernel"])
     if not g or "FETCH_SIZE" not in counters[g[0]] or "WRITE_SIZE" not in counters[g[0]]:
         return None
-    cal_f = copy_scale(counters, "FETCH_SIZE", copy_kib)
-    cal_w = copy_scale(counters, "WRITE_SIZE", copy_kib)
+    cal_f = copy_scale(directories, "FETCH_SIZE", copy_kib)
+    cal_w = copy_scale(directories, "WRITE_SIZE", copy_kib)
     sf = cal_f[1] if cal_f else 1.0
     sw = cal_w[1] if cal_w else 1.0
     lines = ["HBM-side traffic of the PCMM kernels on the %s workload, from rocprofv3 counters" % workload,
@@ -327,9 +335,7 @@ def streaming_summary(trace_dir: Optional[str], fetch_dir: str, write_dir: str, 
     f = read_grouped(fetch_dir, "counter_collection.csv")
     w = read_grouped(write_dir, "counter_collection.csv")
     t = read_grouped(trace_dir, "kernel_trace.csv") if trace_dir else {}
-    flat_f = {k[0] + "@%d" % k[1]: {"FETCH_SIZE": v.get("FETCH_SIZE", [])} for k, v in f.items()}
-    flat_w = {k[0] + "@%d" % k[1]: {"WRITE_SIZE": v.get("WRITE_SIZE", [])} for k, v in w.items()}
-    cal_f, cal_w = copy_scale(flat_f, "FETCH_SIZE", copy_kib), copy_scale(flat_w, "WRITE_SIZE", copy_kib)
+    cal_f, cal_w = copy_scale([fetch_dir], "FETCH_SIZE", copy_kib), copy_scale([write_dir], "WRITE_SIZE", copy_kib)
     sf, sw = (cal_f[1] if cal_f else 1.0), (cal_w[1] if cal_w else 1.0)
     lines = ["HBM-side traffic and achieved rates of the streaming kernels (rocprofv3), per launch, by kernel and grid size", "",
              "commands (from /tmp with TMPDIR=/tmp, R = repository root):"] + ["  " + c for c in commands] + [""]
@@ -380,7 +386,8 @@ def main(argv: Optional[Sequence[str]] = None) -> int:
     if args.pmc:
         counters, durations = merge_counters(args.pmc)
         put("_hbm_traffic.txt", traffic_summary(args.workload, fig, counters,
-                                                [c for c in pmc_cmds if "FETCH_SIZE" in c or "WRITE_SIZE" in c], args.copy_kib))
+                                                [c for c in pmc_cmds if "FETCH_SIZE" in c or "WRITE_SIZE" in c], args.copy_kib,
+                                                args.pmc))
         put("_counters.txt", counter_summary(args.workload, fig, counters, durations,
                                              [c for c in pmc_cmds if "FETCH_SIZE" not in c and "WRITE_SIZE" not in c]))
     if args.streaming_out:

@@ -31,13 +31,14 @@ def test_captured_run_of_the_wide_workload():
     g = counters["gemm_shortk_kernel<7, 2, 2>"]
     assert {"FETCH_SIZE", "WRITE_SIZE", "GRBM_GUI_ACTIVE", "SQ_VALU_MFMA_BUSY_CYCLES"} <= set(g)
     # the calibration copy moves 1 GiB each way: FETCH_SIZE counts half of it, WRITE_SIZE all of it
-    got, scale = rs.copy_scale(counters, "FETCH_SIZE", float(1 << 20))
+    dirs = [os.path.join(GOLD, d) for d in ("fetch", "write", "cnt")]
+    got, scale = rs.copy_scale(dirs, "FETCH_SIZE", float(1 << 20))
     assert abs(scale - 2.0) < 0.01
-    got, scale = rs.copy_scale(counters, "WRITE_SIZE", float(1 << 20))
+    got, scale = rs.copy_scale(dirs, "WRITE_SIZE", float(1 << 20))
     assert abs(scale - 1.0) < 0.01
     fig = rs.workload_figures("wide_pc_attn")
     assert fig["mfma_kernel"] == "gemm_shortk_kernel" and fig["int8_ops"] == 2.0 * 4096 * 128 * 131072 * 6 * 14
-    text = rs.traffic_summary("wide_pc_attn", fig, counters, ["rocprofv3 --pmc FETCH_SIZE ..."], float(1 << 20))
+    text = rs.traffic_summary("wide_pc_attn", fig, counters, ["rocprofv3 --pmc FETCH_SIZE ..."], float(1 << 20), dirs)
     line = [x for x in text.splitlines() if x.startswith("traffic_bytes_per_launch=")]
     assert len(line) == 1
     traffic = float(line[0].split("=")[1])
@@ -71,7 +72,8 @@ def test_hand_made_counters_give_the_expected_figures(tmp_path):
 
     _write_csv(str(tmp_path / "f" / "h" / "1_counter_collection.csv"), hdr, [
         row(1, "__amd_rocclr_copyBuffer", "FETCH_SIZE", 262144.0),           # the 1 GiB copy counted as 256 MiB: scale 4
-        row(2, gk, "FETCH_SIZE", 1000.0), row(3, gk, "FETCH_SIZE", 3000.0)])
+        row(2, gk, "FETCH_SIZE", 1000.0), row(3, gk, "FETCH_SIZE", 3000.0),
+        row(4, "__amd_rocclr_copyBuffer", "FETCH_SIZE", 9999999.0)])         # a later, larger copy is not the calibration
     _write_csv(str(tmp_path / "w" / "h" / "2_counter_collection.csv"), hdr, [
         row(1, "__amd_rocclr_copyBuffer", "WRITE_SIZE", 2097152.0),          # counted twice: scale 0.5
         row(2, gk, "WRITE_SIZE", 8000.0), row(3, gk, "WRITE_SIZE", 8000.0)])
@@ -79,7 +81,7 @@ def test_hand_made_counters_give_the_expected_figures(tmp_path):
         row(2, gk, "GRBM_GUI_ACTIVE", 8.0e6, 0, 1000000), row(2, gk, "SQ_VALU_MFMA_BUSY_CYCLES", 5.12e8, 0, 1000000)])
     counters, durations = rs.merge_counters([str(tmp_path / d) for d in ("f", "w", "c")])
     fig = rs.workload_figures("attn_proj")
-    text = rs.traffic_summary("attn_proj", fig, counters, [], float(1 << 20))
+    text = rs.traffic_summary("attn_proj", fig, counters, [], float(1 << 20), [str(tmp_path / d) for d in ("f", "w", "c")])
     # mean FETCH 2000 KiB x 4 + mean WRITE 8000 KiB x 0.5 = 12000 KiB
     assert "traffic_bytes_per_launch=%d" % (12000 * 1024) in text
     text = rs.counter_summary("attn_proj", fig, counters, durations, [])
