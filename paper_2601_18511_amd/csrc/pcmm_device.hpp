@@ -131,7 +131,9 @@ __device__ __forceinline__ void reduce_f64(const int (&a)[R][E], double q, doubl
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        const double v = rr[r] < 0.0 ? rr[r] + q : rr[r];
+        // lift a negative remainder by q without a compare and selects: |rr| <= 0.6 q, so rr / q lies in (-1, 1) and
+        // its floor is -1 for every negative rr (the product cannot round to zero: |rr| >= 1) and 0 otherwise
+        const double v = __builtin_fma(-__builtin_floor(rr[r] * invq), q, rr[r]);
         // v is an integer in [0, 2^52): adding 2^52 places it in the low mantissa bits
         res[r] = (uint64_t)__double_as_longlong(v + 4503599627370496.0) & 0x000FFFFFFFFFFFFFull;
     }

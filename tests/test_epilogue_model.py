@@ -51,8 +51,9 @@ def reduce_model(acc, q: int, mode: int) -> int:
         X = r * B
         qh = rint((X + c[g]) * invq)
         r = fma(-qh, qd, X) + c[g]
-    if r < 0.0:
-        r = r + qd
+    lift = float(np.floor(r * invq))          # -1 for a negative remainder, 0 otherwise (|r| <= 0.6 q)
+    assert lift == (-1.0 if r < 0.0 else 0.0)
+    r = fma(-lift, qd, r)
     assert r == int(r) and 0 <= r < 2 ** 52
     return int(r)
 
