@@ -66,12 +66,13 @@ __device__ __forceinline__ double reduce(double v, double q, double invq)
 // Inputs of magnitude <= q/2; outputs of magnitude <= 1.375 q.
 __device__ __forceinline__ void ntt_forward(double *s, const double *__restrict__ fwd, int N, double q, double invq)
 {
-    int t = N;
+    int lt = 31 - __builtin_clz((unsigned)N);             // log2 of the butterfly span t
     for (int m = 1; m < N; m <<= 1) {
-        t >>= 1;
+        --lt;
+        const int t = 1 << lt;
         for (int bf = threadIdx.x; bf < N / 2; bf += kThreads) {
-            const int i = bf / t, jj = bf - i * t;
-            const int j = 2 * i * t + jj;
+            const int i = bf >> lt, jj = bf & (t - 1);
+            const int j = (i << (lt + 1)) + jj;
             const double S = fwd[m + i];
             const double U = reduce(s[j], q, invq);
             const double V = mulmod(S, s[j + t], q, invq);
@@ -151,22 +152,22 @@ __global__ __launch_bounds__(kThreads) void mac_intt_kernel(const double *__rest
     __syncthreads();
     const double *inv = inv_tables + (int64_t)limb * N;
     // the two transforms run stage by stage side by side (one barrier per stage for both)
-    int t = 1;
+    int lt = 0;                                            // log2 of the butterfly span t
     for (int mm = N; mm > 1; mm >>= 1) {
-        const int h = mm >> 1;
+        const int h = mm >> 1, t = 1 << lt;
         for (int bf = threadIdx.x; bf < N; bf += kThreads) {          // N butterflies: N/2 per polynomial
             const int half = bf >= N / 2;
             const int b2 = bf - half * (N / 2);
-            const int i = b2 / t, jj = b2 - i * t;
+            const int i = b2 >> lt, jj = b2 & (t - 1);
             double *s = lds + half * N;
-            const int j = 2 * i * t + jj;
+            const int j = (i << (lt + 1)) + jj;
             const double S = inv[h + i];
             const double U = s[j], V = s[j + t];
             s[j] = reduce(U + V, q, invq);
             s[j + t] = mulmod(S, U - V, q, invq);
         }
         __syncthreads();
-        t <<= 1;
+        ++lt;
     }
     uint64_t *o = out + ((int64_t)limb * Mp + m) * 2 * N;
     for (int n = threadIdx.x; n < 2 * N; n += kThreads) {
