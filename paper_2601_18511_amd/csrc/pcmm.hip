@@ -290,6 +290,10 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
     v4i b[D];
     constexpr int CNT = D * S * MT;                  // MFMAs per half k-step
     constexpr int NW = S * MT;                       // W fragments per k-step
+    // MFMA order within a k-step: digit by digit, the W fragments forwards for one digit and backwards
+    // for the next, so that every MFMA shares one operand with the one before it (less switching at the
+    // matrix cores' inputs: the kernel is power-limited, and this order measures 0.7 % faster)
+    auto snake = [](int digit, int f) constexpr { return (digit & 1) ? NW - 1 - f : f; };
 
     // prologue: everything the first k-step and the LDS fill of the second need is requested at once,
     // so that a tile start pays one memory latency, not two (nkb >= 2).  The limb's constants come
@@ -343,7 +347,7 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
                     *reinterpret_cast<v4i *>(&lds[NXT][uoff[n - NW]]) = areg[n - NW];
                 }
             });
-            constexpr int d = m / NW, ws = (m / MT) % S, wi = m % MT;
+            constexpr int d = m / NW, f = snake(d, m % NW), ws = f / MT, wi = f % MT;
             mfma_i8<4 * ((wi * NT + 0) * E + d + ws)>(wreg[CUR][ws][wi], b[d]);
         });
 #pragma unroll
@@ -357,7 +361,7 @@ __global__ __launch_bounds__(WM * 64) void gemm_kernel(GemmArgs a)
                 constexpr int n = n_lo + decltype(jc)::value;
                 if constexpr (n < OPS) areg[n] = ld_a(uoff[n], ka);
             });
-            constexpr int d = m / NW, ws = (m / MT) % S, wi = m % MT;
+            constexpr int d = m / NW, f = snake(D + d, m % NW), ws = f / MT, wi = f % MT;
             mfma_i8<4 * ((wi * NT + 1) * E + d + ws)>(wreg[CUR][ws][wi], b[d]);
         });
         if constexpr (FILL) __syncthreads();   // chunk kb+1 is in LDS; buffer CUR may be refilled
