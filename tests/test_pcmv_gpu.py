@@ -46,7 +46,7 @@ def test_random_shapes_bit_exact(gpu_device, Mp, Kp, N, bits, L, wmax):
     assert (got == want).all(), int((got != want).sum())
 
 
-@pytest.mark.parametrize("bits,N", [(50, 256), (36, 1024), (24, 64), (50, 4096)])
+@pytest.mark.parametrize("bits,N", [(50, 256), (36, 1024), (24, 64), (50, 4096), (36, 4096), (24, 4096), (37, 4096)])
 def test_extreme_values(gpu_device, bits, N):
     """Plaintext coefficients at +-max, residues at 0, 1, q-1, q/2: the largest products and sums the exact
     double-precision arithmetic has to carry."""
@@ -66,6 +66,25 @@ def test_extreme_values(gpu_device, bits, N):
         ct[j] = pats[rng.integers(0, len(pats), size=(Kp, 2, N))]
         ct[j, 0, 0, :] = q - 1
         ct[j, 0, 1, :] = 0
+    got = _run_gpu(pt, ct, primes, bits, gpu_device)
+    want = pcmv_oracle(pt, ct, primes)
+    assert (got == want).all(), int((got != want).sum())
+
+
+@pytest.mark.parametrize("bits", [36, 44])
+def test_long_accumulation_at_the_paper_degree(gpu_device, bits):
+    """Many input ciphertexts per output at ring degree 4096, all values extreme: for primes below 2^36 the kernel adds
+    the products up without reducing (and never reduces a sum inside the inverse transform); above, it reduces."""
+    from oracle import pcmv_oracle
+
+    rng = np.random.default_rng(bits)
+    N, Mp, Kp = 4096, 1, 24
+    primes = pi.ntt_primes(bits, 2 * N, 1)
+    wmax = (1 << 31) - 1
+    pt = np.where(rng.integers(0, 2, size=(Mp, Kp, N)) == 1, wmax, -wmax).astype(np.int64)
+    q = primes[0]
+    pats = np.array([q - 1, q // 2, q // 2 + 1, 1], dtype=np.uint64)
+    ct = pats[rng.integers(0, len(pats), size=(1, Kp, 2, N))]
     got = _run_gpu(pt, ct, primes, bits, gpu_device)
     want = pcmv_oracle(pt, ct, primes)
     assert (got == want).all(), int((got != want).sum())
