@@ -169,7 +169,8 @@ def pcmv_rates(pkg, pi, torch, dev, copy_GBs: float, iters: int = 10, check: boo
         ct = torch.stack([torch.randint(0, q, (Kp, 2, N), dtype=torch.int64, device=dev, generator=g) for q in primes])
         res = torch.empty((L, Mp, 2, N), dtype=torch.int64, device=dev)
         stream = torch.cuda.current_stream()
-        pkg.pcmv_run(plan, ct, res, stream)
+        for _ in range(3):
+            pkg.pcmv_run(plan, ct, res, stream)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
         for _ in range(iters):

@@ -325,7 +325,7 @@ def counter_summary(workload: str, fig: dict, counters, durations, commands: Seq
     return "\n".join(lines) + "\n"
 
 
-STREAMING = re.compile(r"^(split_kernel|transpose_u64_kernel|slot_rearrange_kernel|ntt_kernel|mac_intt\w*|pack_w_kernel)")
+STREAMING = re.compile(r"^(split_kernel|transpose_u64_kernel|slot_rearrange_kernel|ntt\w*_kernel|mac_intt\w*|pack_w_kernel)")
 
 
 def streaming_summary(trace_dir: Optional[str], fetch_dir: str, write_dir: str, commands: Sequence[str],
