@@ -90,6 +90,42 @@ def test_long_accumulation_at_the_paper_degree(gpu_device, bits):
     assert (got == want).all(), int((got != want).sum())
 
 
+@pytest.mark.parametrize("Mp,Kp,L,bits", [(700, 1, 3, 36), (300, 1, 2, 50), (1025, 2, 1, 36), (345, 3, 3, 44)])
+def test_work_queue_covers_every_polynomial(gpu_device, Mp, Kp, L, bits):
+    """Ring degree 4096 with more output polynomials than persistent work-groups (two per compute unit), so that the
+    work queue hands polynomials out and work-groups cross from one limb to the next: every output must equal what
+    plans of at most 100 rows produce (those run one polynomial per work-group, the case the oracle tests cover), and
+    a row of each limb is checked against the oracle directly."""
+    import torch
+
+    import paper_2601_18511_amd as pkg
+    from oracle import pcmv_oracle_rows
+
+    N = 4096
+    rng = np.random.default_rng(Mp + Kp)
+    primes = pi.ntt_primes(bits, 2 * N, L)
+    pt, ct = _case(rng, Mp, Kp, N, primes, 1 << 15)
+    got = _run_gpu(pt, ct, primes, bits, gpu_device)
+    for j, q in enumerate(primes):
+        assert (got[j] < np.uint64(q)).all()              # also: nothing left at the fill value
+    for r0 in range(0, Mp, 100):
+        part = _run_gpu(pt[r0:r0 + 100], ct, primes, bits, gpu_device)
+        assert (got[:, r0:r0 + 100] == part).all(), r0
+    rows = [0, Mp // 2, Mp - 1]
+    want = pcmv_oracle_rows(pt[rows], ct, primes, list(range(len(rows))))
+    assert (got[:, rows] == want).all()
+    # the same plan again, twice in a row on one stream: the queue is reset by each run
+    plan = pkg.pcmv_plan_create(torch.from_numpy(pt.astype(np.int32)).to(gpu_device), primes, bits)
+    ct_dev = torch.from_numpy(ct.view(np.int64)).to(gpu_device)
+    outs = [torch.full((L, Mp, 2, N), -1, dtype=torch.int64, device=gpu_device) for _ in range(2)]
+    for o in outs:
+        pkg.pcmv_run(plan, ct_dev, o)
+    torch.cuda.synchronize()
+    pkg.pcmv_plan_destroy(plan)
+    for o in outs:
+        assert (o.cpu().numpy().view(np.uint64) == got).all()
+
+
 def test_monomial_plaintexts_shift_the_ciphertext(gpu_device):
     rng = np.random.default_rng(5)
     N = 512
