@@ -383,7 +383,7 @@ __global__ __launch_bounds__(kThreads, 2) void mac_intt4096_kernel(const double 
     constexpr uint32_t PB = N * 8;                    // bytes of one polynomial of doubles
     __shared__ double lds[2 * kLdsPoly4096];          // component a, component b
     __shared__ uint32_t queue_word;
-    const int T = threadIdx.x, A = T >> 4, B = T & 15;
+    const int T = threadIdx.x;
     const uint32_t toff = (uint32_t)T * 8u;
     uint32_t blk = blockIdx.x;
     if (blk >= total) return;
@@ -417,7 +417,7 @@ __global__ __launch_bounds__(kThreads, 2) void mac_intt4096_kernel(const double 
             invq = lc[limb].invq;
             if constexpr (KP1) {
                 load_tw(tw1, irs, 256, T);            // pass 1: table entries 2048 + 8 T .., 1024 + 4 T .., 512 + 2 T .., 256 + T
-                load_tw(tw2, irs, 16, A);             // pass 2: 128 + 8 A .., 64 + 4 A .., 32 + 2 A .., 16 + A
+                load_tw(tw2, irs, 16, T >> 4);        // pass 2, A = T / 16: 128 + 8 A .., 64 + 4 A .., 32 + 2 A .., 16 + A
 #pragma unroll
                 for (int e = 0; e < 16; ++e) xa[e] = ld1(crs, toff, 2048u * e);
 #pragma unroll
