@@ -114,3 +114,30 @@ def test_streaming_summary_groups_by_kernel_and_grid():
     assert int(cols[1]) == 6291456 and int(cols[2]) == 12             # grid size; launches in the trace
     assert abs(float(cols[5]) - 0.75) < 0.01 and abs(float(cols[6]) - 0.656) < 0.01   # A read, digit planes written (GiB)
     assert 4500 < float(cols[7]) < 6500
+
+
+def test_streaming_summary_lists_the_transform_kernels_of_both_decode_shapes(tmp_path):
+    """Two instantiations of one persistent kernel launch the same grid; the template arguments keep them apart."""
+    hdr = ["Correlation_Id", "Dispatch_Id", "Agent_Id", "Queue_Id", "Process_Id", "Thread_Id", "Grid_Size", "Kernel_Id",
+           "Kernel_Name", "Workgroup_Size", "LDS_Block_Size", "Scratch_Size", "VGPR_Count", "Accum_VGPR_Count", "SGPR_Count",
+           "Counter_Name", "Counter_Value", "Start_Timestamp", "End_Timestamp"]
+    ns = "void (anonymous namespace)::"
+    mac1 = ns + "mac_intt4096_kernel<true, true>(double const*, double const*, unsigned long*, double const*, (anonymous namespace)::LimbDev const*, unsigned int, int, unsigned int, unsigned int*)"
+    mac4 = mac1.replace("<true, true>", "<true, false>")
+    fwd = ns + "ntt4096_kernel<0, true>(void const*, double*, double const*, (anonymous namespace)::LimbDev const*, long, unsigned int*, unsigned int)"
+
+    def rows(counter, scale):
+        def row(disp, kernel, grid, kib, t1):
+            return [disp, disp, "Agent 1", 1, 7, 7, grid, 1, kernel, 256, 0, 0, 8, 0, 32, counter, kib * scale, 0, t1]
+        return [row(1, "__amd_rocclr_copyBuffer", 1 << 20, float(1 << 20), 400000),
+                row(2, fwd, 1024, 64.0, 6000), row(3, mac1, 131072, 262144.0, 200000), row(4, mac4, 131072, 1048576.0, 400000)]
+
+    _write_csv(str(tmp_path / "f" / "h" / "1_counter_collection.csv"), hdr, rows("FETCH_SIZE", 0.5))
+    _write_csv(str(tmp_path / "w" / "h" / "2_counter_collection.csv"), hdr, rows("WRITE_SIZE", 1.0))
+    text = rs.streaming_summary(None, str(tmp_path / "f"), str(tmp_path / "w"), [], float(1 << 20), [])
+    got = {x.split("  ")[0].strip(): x.split() for x in text.splitlines() if "4096_kernel" in x}
+    assert set(got) == {"mac_intt4096_kernel<true, true>", "mac_intt4096_kernel<true, false>", "ntt4096_kernel<0, true>"}
+    one = got["mac_intt4096_kernel<true, true>"]
+    # 256 MiB read (the counter halves it, the calibration doubles it back) + 256 MiB written in 0.2 ms
+    assert abs(float(one[-3]) - 0.25) < 1e-3 and abs(float(one[-2]) - 0.25) < 1e-3
+    assert abs(float(one[-1]) - 2 * 268435456 / 0.2e-3 / 1e9) < 1.0
