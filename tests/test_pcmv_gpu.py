@@ -126,6 +126,29 @@ def test_work_queue_covers_every_polynomial(gpu_device, Mp, Kp, L, bits):
         assert (o.cpu().numpy().view(np.uint64) == got).all()
 
 
+@pytest.mark.parametrize("bits,Kp", [(36, 4096), (50, 1024), (24, 4096)])
+def test_longest_accumulation_against_a_closed_form(gpu_device, bits, Kp):
+    """The largest number of input ciphertexts per output the library takes (4096), at ring degree 4096.  The schoolbook
+    oracle would need hours; constant plaintext polynomials make the ring product a scalar product, out = sum_k c_k ct_k
+    mod q, which int64 arithmetic computes exactly -- while the kernel still multiplies and adds full-size residues,
+    because the transform of the constant c is c / N mod q at every point."""
+    N, Mp = 4096, 2
+    rng = np.random.default_rng(bits * 7 + Kp)
+    primes = pi.ntt_primes(bits, 2 * N, 1)
+    q = int(primes[0])
+    c = rng.integers(-1000, 1001, size=(Mp, Kp), dtype=np.int64)
+    pt = np.zeros((Mp, Kp, N), dtype=np.int64)
+    pt[:, :, 0] = c
+    ct = rng.integers(0, q, size=(1, Kp, 2, N), dtype=np.uint64)
+    got = _run_gpu(pt, ct, primes, bits, gpu_device)
+    x = ct[0].astype(np.int64)                                   # residues below 2^50, |c| <= 1000: products below 2^60
+    for m in range(Mp):
+        acc = np.zeros((2, N), dtype=np.int64)
+        for k in range(Kp):
+            acc = (acc + int(c[m, k]) * x[k]) % q                # numpy's % is non-negative for a positive modulus
+        assert (got[0, m] == acc.astype(np.uint64)).all(), m
+
+
 def test_monomial_plaintexts_shift_the_ciphertext(gpu_device):
     rng = np.random.default_rng(5)
     N = 512
